@@ -1,0 +1,142 @@
+/*
+ * pqkm.h -- C ABI of the PQk-means iteration for AMD MI355X (gfx950).
+ *
+ * One PQk-means iteration (Alg. 1, linear-scan branch) is an assignment step
+ * (Eq. 5: every PQ code takes the nearest of K PQ-coded centers by squared
+ * symmetric distance, Eq. 3) followed by the sparse-voting update (Eq. 7-8:
+ * per center and subspace, a 256-bin histogram of the members' subcodes and
+ * the subcodeword minimising the count-weighted table sum).
+ *
+ * Conventions common to every entry point
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer to
+ *     memory owned by the caller (e.g. torch.Tensor.data_ptr()) on the device
+ *     that is current when the call is made.  Arrays are dense, row-major,
+ *     unpadded.  The library keeps no pointer after the work it enqueued ends.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on `stream` and return; they never synchronise
+ *     and allocate or free nothing.  Results are valid once `stream` reaches
+ *     the end of the enqueued work.
+ *   - `workspace` is device scratch of at least
+ *     pqkm_workspace_bytes(N, M, K) bytes, 256-byte aligned, used only during
+ *     the call's enqueued work.  Two calls that overlap in time on different
+ *     streams need different workspaces.
+ *   - Subcode/center indices are 0..255 (the paper's 1..L with L = 256,
+ *     Sec. 2.2).  `codes` must be 4-byte aligned when M is a multiple of 4.
+ *   - Arguments are validated on the host before anything is launched; on an
+ *     error nothing has been enqueued and outputs are untouched.
+ *   - Floating point: table entries are fp32; the symmetric distance is an
+ *     fp32 running sum over m = 0..M-1 in ascending order, one IEEE add each;
+ *     the vote accumulates in fp32 with one fused multiply-add per non-zero
+ *     bin in ascending bin order.  Ties in either argmin go to the lowest
+ *     index.  With these rules the result is unique, so a second
+ *     implementation can be compared bit for bit.
+ */
+#ifndef PQKM_H
+#define PQKM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PQKM_OK = 0,
+    PQKM_ERR_NULL = 1,      /* a required pointer is NULL                                  */
+    PQKM_ERR_SHAPE = 2,     /* N < 0, K < 1, M < 1 or M > 64, Ds < 1, iters < 0, bad align */
+    PQKM_ERR_WORKSPACE = 3, /* workspace NULL / misaligned / smaller than required         */
+    PQKM_ERR_DEVICE = 4     /* not a gfx950 device, or a HIP call failed                   */
+} pqkm_status;
+
+/* Static, NUL-terminated description of a status code. */
+const char *pqkm_status_string(pqkm_status status);
+
+/*
+ * Bytes of device scratch that pqkm_assign / pqkm_update / pqkm_fit need for
+ * a problem of N codes, M subspaces, K centers.  Pure host arithmetic (no HIP
+ * call).  Returns 0 for invalid shapes.
+ */
+size_t pqkm_workspace_bytes(int64_t N, int32_t M, int32_t K);
+
+/*
+ * Distance matrices among codewords (Sec. 2.2):
+ *   tables[m][i][j] = || codewords[m][i][:] - codewords[m][j][:] ||^2
+ * accumulated in fp64 over ascending dimension in the direct-difference form
+ * and rounded once to fp32, so the diagonal is exactly 0 and each matrix is
+ * bitwise symmetric.
+ *   codewords  [M][256][Ds] fp32, in
+ *   tables     [M][256][256] fp32, out
+ */
+pqkm_status pqkm_build_tables(const float *codewords, int32_t M, int32_t Ds, float *tables,
+                              void *stream);
+
+/*
+ * Assignment step (Eq. 5 with the squared symmetric distance of Eq. 3):
+ *   assign[n] = argmin_k  sum_{m} tables[m][codes[n][m]][centers[k][m]]
+ * lowest k on ties.
+ *   codes    [N][M] u8, in          centers [K][M] u8, in
+ *   tables   [M][256][256] fp32, in (row = the code's subcode, column = the center's)
+ *   assign   [N] i32, out           dist    [N] fp32, out, may be NULL (the minimum itself)
+ * N = 0 is legal and does nothing.
+ */
+pqkm_status pqkm_assign(const uint8_t *codes, int64_t N, int32_t M, const uint8_t *centers,
+                        int32_t K, const float *tables, int32_t *assign, float *dist,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Update step by sparse voting (Eq. 7 then Eq. 8):
+ *   hist[k][m][j] = #{ n : assign[n] = k and codes[n][m] = j },  counts[k] = #{ n : assign[n] = k }
+ *   centers[k][m] <- argmin_l  sum_{j : hist[k][m][j] > 0} hist[k][m][j] * tables[m][j][l]
+ * lowest l on ties; a center with counts[k] = 0 keeps its code.
+ *   assign   [N] i32, in; every value must lie in [0, K) (not checked on the device:
+ *            out-of-range values are ignored by the histogram, making counts inconsistent)
+ *   centers  [K][M] u8, in/out
+ *   hist     [K][M][256] u32, out, may be NULL (then it lives in the workspace)
+ *   counts   [K] u32, out, may be NULL
+ */
+pqkm_status pqkm_update(const uint8_t *codes, int64_t N, int32_t M, const int32_t *assign,
+                        int32_t K, const float *tables, uint8_t *centers, uint32_t *hist,
+                        uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Alg. 1 with the linear scan and a fixed iteration count:
+ *   repeat iters times { pqkm_assign ; pqkm_update }.
+ * Init() is the caller's: `centers` holds the initial centers on entry and the
+ * centers after the last update on return.  `assign` receives the result of
+ * the LAST assignment step, i.e. taken against the centers as they were before
+ * the last update (the order of Alg. 1).  `hist` / `counts` (may be NULL) are
+ * those of the last update.  iters = 0 leaves everything untouched.
+ */
+pqkm_status pqkm_fit(const uint8_t *codes, int64_t N, int32_t M, const float *tables, int32_t K,
+                     uint8_t *centers, int32_t iters, int32_t *assign, uint32_t *hist,
+                     uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning and measurement hooks (not part of the method).
+ *
+ * pqkm_set_option: process-wide integer knobs, by name (host string).  Unknown
+ * name or out-of-range value -> PQKM_ERR_SHAPE.  Names:
+ *   "assign_kernel"      0 = choose automatically (default), 1 = force the generic
+ *                        scan that reads the tables through the cache hierarchy,
+ *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
+ *   "scan_variant"       0 = default launch shape of the LDS-tiled scan, 1..64 =
+ *                        one specific compiled shape (for tuning sweeps)
+ *   "launch_codes_log2"  the scan is issued in launches of 2^value codes (default 26)
+ *   "profile"            1 = bracket every scan-kernel launch with a pair of HIP
+ *                        events on the caller's stream (events are created on
+ *                        first use and reused; this is the one place the library
+ *                        creates HIP objects), 0 = off (default)
+ *
+ * pqkm_profile_read: waits for the recorded stop events, returns the summed
+ * elapsed time of the bracketed scan launches in milliseconds and their number,
+ * and resets the record.  The only entry point that blocks the host.
+ *   total_ms, launches   host pointers, out
+ */
+pqkm_status pqkm_set_option(const char *name, int32_t value);
+pqkm_status pqkm_profile_read(double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQKM_H */

@@ -1,0 +1,12 @@
+"""PQk-means iteration on AMD MI355X: thin Python binding over the C ABI of libpqkm.so.
+
+The functions here carry the names of the C entry points (include/pqkm.h) and only marshal
+arguments: torch tensors supply device memory, the current torch stream supplies the HIP
+stream.  Every step of the path runs in the library's HIP kernels; there is no CPU fallback
+-- a missing library raises at import of the first call.
+"""
+from .binding import (PqkmError, assign, build_tables, fit, lib_path, load, profile_read, set_option,
+                      status_string, update, workspace_bytes)
+
+__all__ = ["PqkmError", "assign", "build_tables", "fit", "lib_path", "load", "profile_read", "set_option",
+           "status_string", "update", "workspace_bytes"]

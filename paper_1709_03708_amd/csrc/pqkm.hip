@@ -1,0 +1,335 @@
+// C ABI of the PQk-means iteration for gfx950: argument validation, workspace carving and
+// kernel launches.  Every entry point is declared and documented in include/pqkm.h.
+#include "pqkm.h"
+
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "pqkm_kernels.h"
+
+namespace {
+
+using namespace pqkm;
+
+// ------------------------------------------------------------------ options and profiling state
+struct Options {
+    int assign_kernel = 0;   // 0 auto, 1 generic, 2 tiled
+    int scan_variant = 0;    // 0 auto, else a specific instantiation (tuning)
+    int profile = 0;         // bracket scan kernels with events
+    int64_t launch_codes = (int64_t)1 << 26;   // codes per scan launch
+};
+Options g_opt;
+std::mutex g_mu;
+
+struct EventPair { hipEvent_t a, b; };
+std::vector<EventPair> g_pool;      // all events ever created
+size_t g_used = 0;                  // pairs recorded since the last read
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
+
+struct Carve {
+    size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, total;
+};
+
+Carve carve(int64_t /*N*/, int M, int K)
+{
+    Carve c{};
+    size_t off = 0;
+    c.img_off = off;
+    if (tiled_M(M)) {
+        int TK = 128 / M;
+        size_t ntiles = ((size_t)K + TK - 1) / TK;
+        c.img_bytes = ntiles * (size_t)TILE_BYTES;
+    }
+    off += align256(c.img_bytes);
+    c.hist_off = off;
+    c.hist_bytes = (size_t)K * M * L * sizeof(uint32_t);
+    off += align256(c.hist_bytes);
+    c.counts_off = off;
+    c.counts_bytes = (size_t)K * sizeof(uint32_t);
+    off += align256(c.counts_bytes);
+    c.total = off;
+    return c;
+}
+
+bool shape_ok(int64_t N, int M, int K) { return N >= 0 && K >= 1 && M >= 1 && M <= 64; }
+
+pqkm_status check_device()
+{
+    static thread_local int checked_dev = -1;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PQKM_ERR_DEVICE;
+    if (dev == checked_dev) return PQKM_OK;
+    hipDeviceProp_t p;
+    if (hipGetDeviceProperties(&p, dev) != hipSuccess) return PQKM_ERR_DEVICE;
+    if (strncmp(p.gcnArchName, "gfx950", 6) != 0) return PQKM_ERR_DEVICE;
+    checked_dev = dev;
+    return PQKM_OK;
+}
+
+pqkm_status launched()
+{
+    return hipGetLastError() == hipSuccess ? PQKM_OK : PQKM_ERR_DEVICE;
+}
+
+pqkm_status check_workspace(const void* ws, size_t bytes, size_t need)
+{
+    if (need == 0) return PQKM_OK;
+    if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || bytes < need) return PQKM_ERR_WORKSPACE;
+    return PQKM_OK;
+}
+
+// ------------------------------------------------------------------ scan launch
+template <int M, int R, int THREADS, bool PF>
+void launch_scan(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                 hipStream_t st)
+{
+    using S = ScanShape<M>;
+    constexpr int C = (THREADS / S::LPS) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan_kernel<M, R, THREADS, PF>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
+                       img, ntiles, assign, dist);
+}
+
+template <int M>
+void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+                   float* dist, hipStream_t st);
+
+template <>
+void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+                      float* dist, hipStream_t st)
+{
+    switch (variant) {
+        case 1: launch_scan<4, 16, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 2: launch_scan<4, 32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 3: launch_scan<4, 16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 4: launch_scan<4, 24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 5: launch_scan<4, 8, 1024, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 6: launch_scan<4, 12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 7: launch_scan<4, 32, 256, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 8: launch_scan<4, 32, 256, true>(codes, N, img, ntiles, assign, dist, st); break;
+        default: launch_scan<4, 16, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+    }
+}
+template <>
+void launch_scan_M<8>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+                      float* dist, hipStream_t st)
+{
+    launch_scan<8, 8, 512, false>(codes, N, img, ntiles, assign, dist, st);
+}
+template <>
+void launch_scan_M<16>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+                       float* dist, hipStream_t st)
+{
+    launch_scan<16, 4, 512, false>(codes, N, img, ntiles, assign, dist, st);
+}
+template <>
+void launch_scan_M<32>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+                       float* dist, hipStream_t st)
+{
+    launch_scan<32, 2, 512, false>(codes, N, img, ntiles, assign, dist, st);
+}
+
+template <int M>
+pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers, int K, const float* tables,
+                         int32_t* assign, float* dist, float* img, const Options& opt, hipStream_t st)
+{
+    constexpr int TK = 128 / M;
+    int64_t ntiles = ((int64_t)K + TK - 1) / TK;
+    int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
+    hipLaunchKernelGGL((tile_image_kernel<M>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, centers, K,
+                       tables, img, total);
+    if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
+    for (int64_t n0 = 0; n0 < N; n0 += opt.launch_codes) {
+        int64_t cnt = N - n0 < opt.launch_codes ? N - n0 : opt.launch_codes;
+        EventPair ev{};
+        bool prof = false;
+        if (opt.profile) {
+            std::lock_guard<std::mutex> lk(g_mu);
+            if (g_used == g_pool.size()) {
+                EventPair e{};
+                if (hipEventCreate(&e.a) == hipSuccess && hipEventCreate(&e.b) == hipSuccess) g_pool.push_back(e);
+            }
+            if (g_used < g_pool.size()) {
+                ev = g_pool[g_used++];
+                prof = true;
+            }
+        }
+        if (prof) hipEventRecord(ev.a, st);
+        launch_scan_M<M>(opt.scan_variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), (int)ntiles,
+                         assign + n0, dist ? dist + n0 : nullptr, st);
+        if (prof) hipEventRecord(ev.b, st);
+        if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
+    }
+    return PQKM_OK;
+}
+
+pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* centers, int K, const float* tables,
+                        int32_t* assign, float* dist, void* ws, hipStream_t st)
+{
+    if (N == 0) return PQKM_OK;
+    Options opt;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        opt = g_opt;
+    }
+    bool tiled = tiled_M(M) && opt.assign_kernel != 1 && ((uintptr_t)codes & 3) == 0;
+    if (opt.assign_kernel == 2 && !tiled) return PQKM_ERR_SHAPE;
+    if (!tiled) {
+        hipLaunchKernelGGL(assign_generic_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, codes, N, M,
+                           centers, K, tables, assign, dist);
+        return launched();
+    }
+    Carve c = carve(N, M, K);
+    float* img = reinterpret_cast<float*>(static_cast<char*>(ws) + c.img_off);
+    switch (M) {
+        case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, st);
+        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, st);
+        case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, st);
+        default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, st);
+    }
+}
+
+pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* assign, int K, const float* tables,
+                        uint8_t* centers, uint32_t* hist, uint32_t* counts, void* ws, hipStream_t st)
+{
+    Carve c = carve(N, M, K);
+    if (!hist) hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.hist_off);
+    if (!counts) counts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.counts_off);
+    int64_t nh = (int64_t)K * M * L;
+    unsigned zb = (unsigned)((nh + 255) / 256 < 65536 ? (nh + 255) / 256 : 65536);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, hist, nh);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, counts, (int64_t)K);
+    if (N > 0) {
+        const int64_t per = (int64_t)1 << 30;
+        for (int64_t n0 = 0; n0 < N; n0 += per) {
+            int64_t cnt = N - n0 < per ? N - n0 : per;
+            hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st,
+                               codes + n0 * M, cnt, M, assign + n0, K, hist, counts);
+        }
+    }
+    int64_t pairs = (int64_t)K * M;
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st, hist, counts, K, M, tables,
+                       centers);
+    return launched();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pqkm_status_string(pqkm_status s)
+{
+    switch (s) {
+        case PQKM_OK: return "ok";
+        case PQKM_ERR_NULL: return "a required pointer is NULL";
+        case PQKM_ERR_SHAPE: return "invalid shape, size, alignment or option";
+        case PQKM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PQKM_ERR_DEVICE: return "not a gfx950 device, or a HIP call failed";
+    }
+    return "unknown status";
+}
+
+size_t pqkm_workspace_bytes(int64_t N, int32_t M, int32_t K)
+{
+    if (!shape_ok(N, M, K)) return 0;
+    return carve(N, M, K).total;
+}
+
+pqkm_status pqkm_build_tables(const float* codewords, int32_t M, int32_t Ds, float* tables, void* stream)
+{
+    if (!codewords || !tables) return PQKM_ERR_NULL;
+    if (M < 1 || M > 64 || Ds < 1 || Ds > 12288) return PQKM_ERR_SHAPE;
+    pqkm_status s = check_device();
+    if (s != PQKM_OK) return s;
+    hipLaunchKernelGGL(build_tables_kernel, dim3(L, M), dim3(256), (size_t)Ds * sizeof(float), (hipStream_t)stream,
+                       codewords, Ds, tables);
+    return launched();
+}
+
+pqkm_status pqkm_assign(const uint8_t* codes, int64_t N, int32_t M, const uint8_t* centers, int32_t K,
+                        const float* tables, int32_t* assign, float* dist, void* workspace, size_t workspace_bytes,
+                        void* stream)
+{
+    if (!shape_ok(N, M, K)) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    return assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, (hipStream_t)stream);
+}
+
+pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,
+                        const float* tables, uint8_t* centers, uint32_t* hist, uint32_t* counts, void* workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    if (!shape_ok(N, M, K)) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    return update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
+}
+
+pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* tables, int32_t K, uint8_t* centers,
+                     int32_t iters, int32_t* assign, uint32_t* hist, uint32_t* counts, void* workspace,
+                     size_t workspace_bytes, void* stream)
+{
+    if (!shape_ok(N, M, K) || iters < 0) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    for (int it = 0; it < iters; ++it) {
+        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream);
+        if (s != PQKM_OK) return s;
+        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
+        if (s != PQKM_OK) return s;
+    }
+    return PQKM_OK;
+}
+
+pqkm_status pqkm_set_option(const char* name, int32_t value)
+{
+    if (!name) return PQKM_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (strcmp(name, "assign_kernel") == 0) {
+        if (value < 0 || value > 2) return PQKM_ERR_SHAPE;
+        g_opt.assign_kernel = value;
+    } else if (strcmp(name, "scan_variant") == 0) {
+        if (value < 0 || value > 64) return PQKM_ERR_SHAPE;
+        g_opt.scan_variant = value;
+    } else if (strcmp(name, "profile") == 0) {
+        if (value < 0 || value > 1) return PQKM_ERR_SHAPE;
+        g_opt.profile = value;
+    } else if (strcmp(name, "launch_codes_log2") == 0) {
+        if (value < 10 || value > 40) return PQKM_ERR_SHAPE;
+        g_opt.launch_codes = (int64_t)1 << value;
+    } else {
+        return PQKM_ERR_SHAPE;
+    }
+    return PQKM_OK;
+}
+
+pqkm_status pqkm_profile_read(double* total_ms, int64_t* launches)
+{
+    if (!total_ms || !launches) return PQKM_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    double tot = 0.0;
+    for (size_t i = 0; i < g_used; ++i) {
+        if (hipEventSynchronize(g_pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
+        tot += ms;
+    }
+    *total_ms = tot;
+    *launches = (int64_t)g_used;
+    g_used = 0;
+    return PQKM_OK;
+}
+
+}  // extern "C"

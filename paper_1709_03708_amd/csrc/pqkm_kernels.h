@@ -1,0 +1,337 @@
+// HIP kernels for the PQk-means iteration on gfx950 (wave64, 160 KB LDS per CU).
+//
+// Naming follows the paper: A^m are the per-subspace 256x256 distance tables
+// (Sec. 2.2), SDC is the squared symmetric distance (Eq. 3), the assignment is
+// Eq. 5, the histogram Eq. 7 and the vote Eq. 8.
+//
+// Everything here is compiled with -ffp-contract=off: the only fused operation
+// is the explicit fmaf of the vote.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pqkm {
+
+constexpr int L = 256;                    // subcodewords per subspace
+constexpr int TILE_BYTES = 128 * 1024;    // LDS image of one center tile
+constexpr int TILE_F4 = TILE_BYTES / 16;  // the same in float4 units
+constexpr int IDX_NONE = 0x7fffffff;      // "no center improved yet"
+
+// ---------------------------------------------------------------------------------------------
+// Sec. 2.2: A^m[i][j] = || c^m_i - c^m_j ||^2, fp64 accumulation in ascending dimension, direct
+// difference form, one rounding to fp32.  Grid (256, M), block 256: block (i, m), thread j.
+// Codeword i is staged in LDS; codeword j is read with stride Ds (small, cache resident).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void build_tables_kernel(const float* __restrict__ codewords, int Ds,
+                                                           float* __restrict__ tables)
+{
+    extern __shared__ float ci[];
+    const int i = blockIdx.x, m = blockIdx.y, j = threadIdx.x;
+    const float* cw = codewords + (size_t)m * L * Ds;
+    for (int d = j; d < Ds; d += 256) ci[d] = cw[(size_t)i * Ds + d];
+    __syncthreads();
+    const float* cj = cw + (size_t)j * Ds;
+    double acc = 0.0;
+    for (int d = 0; d < Ds; ++d) {
+        double diff = (double)ci[d] - (double)cj[d];
+        double sq = diff * diff;
+        acc = acc + sq;
+    }
+    tables[((size_t)m * L + i) * L + j] = (float)acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic assignment (any M): one lane per code, centers read wave-uniformly, table entries
+// gathered through the cache hierarchy.  Eq. 5 exactly as written: ascending k, strict <.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void assign_generic_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
+                                                             const uint8_t* __restrict__ centers, int K,
+                                                             const float* __restrict__ tables,
+                                                             int32_t* __restrict__ assign, float* __restrict__ dist)
+{
+    int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const uint8_t* x = codes + n * M;
+    float best = INFINITY;
+    int bk = 0;
+    for (int k = 0; k < K; ++k) {
+        const uint8_t* mu = centers + (size_t)k * M;
+        float s = tables[((size_t)0 * L + x[0]) * L + mu[0]];
+        for (int m = 1; m < M; ++m) {
+            float a = tables[((size_t)m * L + x[m]) * L + mu[m]];
+            s = s + a;
+        }
+        if (s < best) {
+            best = s;
+            bk = k;
+        }
+    }
+    assign[n] = bk;
+    if (dist) dist[n] = best;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Center-tile images for the LDS-tiled scan.
+//
+// A tile holds TK = 128 / M consecutive centers.  Its image is laid out exactly as the scan
+// wants it in LDS:   img[tile][m][x][kin] = A^m[x][centers[tile*TK + kin][m]]      (fp32)
+// i.e. for every subspace m and possible code subcode x, one contiguous row of TK entries (one
+// per center of the tile).  A row is TK*4 bytes, a tile 128 KB.  With x in the low address
+// bits, the rows two codes read in the same subspace fall on LDS banks chosen by their
+// subcodes rather than all on the same ones.  Centers past K are padded with +inf, which a
+// strict "<" never selects.  One thread per element, kin fastest, so stores are contiguous.
+// ---------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restrict__ centers, int K,
+                                                         const float* __restrict__ tables, float* __restrict__ img,
+                                                         int64_t total)
+{
+    constexpr int TK = 128 / M;
+    int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    int kin = (int)(e % TK);
+    int x = (int)((e / TK) % L);
+    int m = (int)((e / (TK * L)) % M);
+    int64_t tile = e / ((int64_t)TK * M * L);
+    int64_t k = tile * TK + kin;
+    float v = INFINITY;
+    if (k < K) v = tables[((size_t)m * L + x) * L + centers[k * M + m]];
+    img[e] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS-tiled assignment scan (Eq. 5 over Eq. 3), M in {4, 8, 16, 32}.
+//
+// Work decomposition.  A workgroup keeps C = SLOTS*R codes in registers and walks over all
+// center tiles; each tile image is copied from global memory into LDS once per workgroup and
+// then serves C * TK distance evaluations.  LPS = TK/4 consecutive lanes form a "slot" that
+// works on one code at a time: lane q of the slot reads, for every subspace m, the 16 bytes
+//      tile[m][x_m][4q .. 4q+3]          (one ds_read_b128)
+// so the LPS lanes of a slot read one contiguous row and different slots read different rows:
+// the M gathers per (code, center) of Eq. 3 become M/4 wide LDS reads per lane with no address
+// arithmetic in the loop (the per-code byte offsets of the M rows are computed once and kept
+// in registers when M = 4; for larger M they are rebuilt from the packed code).
+//
+// Each lane sums its 4 centers in ascending m (fp32, unfused) and keeps the running minimum and
+// its index over the centers it sees; since it sees them in ascending k, a strict "<" keeps the
+// lowest index.  At the end the LPS lanes of a slot are merged by (value, index) with xor
+// shuffles -- the wavefront-level argmin -- and lane 0 of the slot writes the result.
+// ---------------------------------------------------------------------------------------------
+template <int M> struct ScanShape {
+    static constexpr int TK = 128 / M;      // centers per tile
+    static constexpr int LPS = TK / 4;      // lanes per slot
+    static constexpr int ROWB = TK * 4;     // bytes per (m, x) row
+    static constexpr int MB = L * ROWB;     // bytes per subspace
+    static constexpr int W = M / 4;         // 32-bit words per packed code
+};
+
+__device__ __forceinline__ float4 lds_read16(const char* base, uint32_t byte_off)
+{
+    return *reinterpret_cast<const float4*>(base + byte_off);
+}
+
+template <int M, int R, int THREADS, bool PREFETCH>
+__global__ __launch_bounds__(THREADS) void assign_scan_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                              const float4* __restrict__ img, int ntiles,
+                                                              int32_t* __restrict__ assign,
+                                                              float* __restrict__ dist)
+{
+    using S = ScanShape<M>;
+    constexpr int SLOTS = THREADS / S::LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;   // float4 per thread per tile fill
+    static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % S::LPS;
+    const int c = tid / S::LPS;
+    const int64_t base = (int64_t)blockIdx.x * C;
+
+    uint32_t pk[R][S::W];
+    float best[R];
+    int idx[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        const uint32_t* cw = reinterpret_cast<const uint32_t*>(codes + n * M);
+#pragma unroll
+        for (int w = 0; w < S::W; ++w) pk[r][w] = cw[w];
+        best[r] = INFINITY;
+        idx[r] = IDX_NONE;
+    }
+    // M = 4: per-code LDS byte offsets, fixed for the whole kernel
+    uint32_t off[R][4];
+    if (M == 4) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) off[r][m] = m * S::MB + ((pk[r][0] >> (8 * m)) & 255u) * S::ROWB + q * 16;
+    }
+
+    float4 pf[NF];
+    if (PREFETCH) {
+#pragma unroll
+        for (int i = 0; i < NF; ++i) pf[i] = img[(size_t)i * THREADS + tid];
+    }
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();                       // everyone is done reading the previous tile
+        if (PREFETCH) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i) tile[i * THREADS + tid] = pf[i];
+        } else {
+            const float4* src = img + (size_t)t * TILE_F4;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) tile[i * THREADS + tid] = src[(size_t)i * THREADS + tid];
+        }
+        __syncthreads();
+        if (PREFETCH && t + 1 < ntiles) {
+            const float4* src = img + (size_t)(t + 1) * TILE_F4;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) pf[i] = src[(size_t)i * THREADS + tid];
+        }
+        const int kb = t * S::TK + q * 4;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float4 s;
+            if (M == 4) {
+                float4 v0 = lds_read16(tb, off[r][0]);
+                float4 v1 = lds_read16(tb, off[r][1]);
+                float4 v2 = lds_read16(tb, off[r][2]);
+                float4 v3 = lds_read16(tb, off[r][3]);
+                s.x = v0.x + v1.x; s.y = v0.y + v1.y; s.z = v0.z + v1.z; s.w = v0.w + v1.w;
+                s.x = s.x + v2.x;  s.y = s.y + v2.y;  s.z = s.z + v2.z;  s.w = s.w + v2.w;
+                s.x = s.x + v3.x;  s.y = s.y + v3.y;  s.z = s.z + v3.z;  s.w = s.w + v3.w;
+            } else {
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    uint32_t x = (pk[r][m / 4] >> (8 * (m % 4))) & 255u;
+                    float4 v = lds_read16(tb, x * S::ROWB + q * 16 + m * S::MB);
+                    if (m == 0) {
+                        s = v;
+                    } else {
+                        s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
+                    }
+                }
+            }
+            float b = best[r];
+            int bi = idx[r];
+            if (s.x < b) { b = s.x; bi = kb; }
+            if (s.y < b) { b = s.y; bi = kb + 1; }
+            if (s.z < b) { b = s.z; bi = kb + 2; }
+            if (s.w < b) { b = s.w; bi = kb + 3; }
+            best[r] = b;
+            idx[r] = bi;
+        }
+    }
+
+    // wavefront-level argmin over the lanes of a slot: smaller value, then smaller index
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float b = best[r];
+        int bi = idx[r];
+#pragma unroll
+        for (int d = S::LPS / 2; d >= 1; d >>= 1) {
+            float ob = __shfl_xor(b, d);
+            int oi = __shfl_xor(bi, d);
+            if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+        }
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (q == 0 && n < N) {
+            assign[n] = (bi == IDX_NONE) ? 0 : bi;
+            if (dist) dist[n] = b;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Zero fill (a kernel, not a memset node, so that callers may capture the calls in a graph).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n; i += stride) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 7: hist[k][m][j] += 1 for every code n with assign[n] = k and codes[n][m] = j; counts[k].
+// Integer atomics: exact and independent of order.  One lane per code.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void histogram_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
+                                                        const int32_t* __restrict__ assign, int K,
+                                                        uint32_t* __restrict__ hist, uint32_t* __restrict__ counts)
+{
+    int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    int k = assign[n];
+    if ((unsigned)k >= (unsigned)K) return;
+    atomicAdd(&counts[k], 1u);
+    const uint8_t* x = codes + n * M;
+    uint32_t* h = hist + (size_t)k * M * L;
+    if ((M & 3) == 0) {
+        const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
+        for (int w = 0; w < M / 4; ++w) {
+            uint32_t p = xw[w];
+            atomicAdd(&h[(size_t)(4 * w + 0) * L + (p & 255u)], 1u);
+            atomicAdd(&h[(size_t)(4 * w + 1) * L + ((p >> 8) & 255u)], 1u);
+            atomicAdd(&h[(size_t)(4 * w + 2) * L + ((p >> 16) & 255u)], 1u);
+            atomicAdd(&h[(size_t)(4 * w + 3) * L + (p >> 24)], 1u);
+        }
+    } else {
+        for (int m = 0; m < M; ++m) atomicAdd(&h[(size_t)m * L + x[m]], 1u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 8: sparse vote.  One wavefront per (center k, subspace m); lane i owns candidates
+// l = 4i..4i+3.  Non-zero bins are visited in ascending j (ballot over 64-bin chunks), each one
+// costing a coalesced 1 KB read of row A^m[j][.] and one fmaf per candidate.  The 256-way argmin
+// is a per-lane ascending strict "<" followed by a (value, index) merge across the wave.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void vote_kernel(const uint32_t* __restrict__ hist,
+                                                   const uint32_t* __restrict__ counts, int K, int M,
+                                                   const float* __restrict__ tables, uint8_t* __restrict__ centers)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= (int64_t)K * M) return;
+    const int k = (int)(pair / M), m = (int)(pair % M);
+    if (counts[k] == 0) return;                                  // empty cluster keeps its code
+    const uint32_t* h = hist + (size_t)pair * L;
+    const float* A = tables + (size_t)m * L * L;
+    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
+    for (int chunk = 0; chunk < 4; ++chunk) {
+        uint32_t hv = h[chunk * 64 + lane];
+        uint64_t mask = __ballot(hv != 0u);
+        while (mask) {
+            int jl = __ffsll((unsigned long long)mask) - 1;
+            mask &= mask - 1;
+            float hf = (float)__shfl(hv, jl);
+            float4 row = *reinterpret_cast<const float4*>(A + (size_t)(chunk * 64 + jl) * L + lane * 4);
+            v0 = fmaf(hf, row.x, v0);
+            v1 = fmaf(hf, row.y, v1);
+            v2 = fmaf(hf, row.z, v2);
+            v3 = fmaf(hf, row.w, v3);
+        }
+    }
+    float b = INFINITY;
+    int bi = IDX_NONE;
+    if (v0 < b) { b = v0; bi = lane * 4; }
+    if (v1 < b) { b = v1; bi = lane * 4 + 1; }
+    if (v2 < b) { b = v2; bi = lane * 4 + 2; }
+    if (v3 < b) { b = v3; bi = lane * 4 + 3; }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        float ob = __shfl_xor(b, d);
+        int oi = __shfl_xor(bi, d);
+        if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+    }
+    if (lane == 0) centers[pair] = (uint8_t)((bi == IDX_NONE) ? 0 : bi);
+}
+
+}  // namespace pqkm

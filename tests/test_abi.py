@@ -1,0 +1,92 @@
+"""The C-ABI library loads and exports every symbol the header declares; host-side argument
+validation fails cleanly without a GPU (no compute is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pqkm.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1709_03708_amd as pq
+
+    if not os.path.exists(pq.lib_path()):
+        from paper_1709_03708_amd import build
+
+        build.build()
+    return pq.load()
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pqkm_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert {"pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_workspace_bytes",
+            "pqkm_status_string", "pqkm_set_option", "pqkm_profile_read"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    seen = {lib.pqkm_status_string(i).decode() for i in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert lib.pqkm_status_string(99).decode() == "unknown status"
+
+
+def test_workspace_bytes_is_host_arithmetic(lib):
+    import paper_1709_03708_amd as pq
+
+    assert pq.workspace_bytes(10, 0, 5) == 0 and pq.workspace_bytes(-1, 4, 5) == 0 and pq.workspace_bytes(1, 4, 0) == 0
+    # M = 4: one 128 KB tile image per 32 centers + histogram + counts
+    b = pq.workspace_bytes(10**6, 4, 1000)
+    assert b >= 32 * 131072 + 1000 * 4 * 256 * 4 + 1000 * 4
+    assert b % 256 == 0
+    assert pq.workspace_bytes(10**9, 4, 10**5) < 2**31     # well under a GiB
+    # a generic M needs no tile images
+    assert pq.workspace_bytes(100, 5, 10) < 131072
+
+
+def test_bad_arguments_are_rejected_before_any_gpu_work(lib):
+    vp = ctypes.c_void_p
+    one = vp(256)        # a non-NULL, aligned dummy address; never dereferenced on these paths
+    null = vp(0)
+    OK, NULL, SHAPE, WS = 0, 1, 2, 3
+    assert lib.pqkm_assign(one, 10, 4, null, 5, one, one, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_assign(one, 10, 4, one, 5, null, one, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_assign(null, 10, 4, one, 5, one, one, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_assign(one, -1, 4, one, 5, one, one, null, one, 1 << 30, null) == SHAPE
+    assert lib.pqkm_assign(one, 10, 0, one, 5, one, one, null, one, 1 << 30, null) == SHAPE
+    assert lib.pqkm_assign(one, 10, 65, one, 5, one, one, null, one, 1 << 30, null) == SHAPE
+    assert lib.pqkm_assign(one, 10, 4, one, 0, one, one, null, one, 1 << 30, null) == SHAPE
+    assert lib.pqkm_assign(one, 10, 4, one, 5, one, one, null, null, 1 << 30, null) == WS
+    assert lib.pqkm_assign(one, 10, 4, one, 5, one, one, null, one, 16, null) == WS
+    assert lib.pqkm_assign(one, 10, 4, one, 5, one, one, null, vp(260), 1 << 30, null) == WS
+    assert lib.pqkm_update(one, 10, 4, null, 5, one, one, null, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_update(one, 10, 4, one, 5, one, null, null, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_update(one, 10, 4, one, 5, one, one, null, null, one, 8, null) == WS
+    assert lib.pqkm_fit(one, 10, 4, one, 5, one, -1, one, null, null, one, 1 << 30, null) == SHAPE
+    assert lib.pqkm_fit(one, 10, 4, null, 5, one, 1, one, null, null, one, 1 << 30, null) == NULL
+    assert lib.pqkm_build_tables(null, 4, 32, one, null) == NULL
+    assert lib.pqkm_build_tables(one, 4, 0, one, null) == SHAPE
+    assert lib.pqkm_build_tables(one, 0, 32, one, null) == SHAPE
+    assert lib.pqkm_set_option(b"no_such_option", 1) == SHAPE
+    assert lib.pqkm_set_option(b"assign_kernel", 7) == SHAPE
+    assert lib.pqkm_set_option(b"assign_kernel", 0) == OK
+    assert lib.pqkm_set_option(None, 0) == NULL
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    import paper_1709_03708_amd.binding as b
+
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libpqkm.so")
+    with pytest.raises(ImportError):
+        b.load()

@@ -1,0 +1,295 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bar: bit-exact for assignments, minimum distances (given identical fp32 tables), histograms,
+counts and updated centers; the tables themselves within 1e-6 relative.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from _util import progress, rand_tables, u32, workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    import oracle
+    import paper_1709_03708_amd as pq
+    import workloads as W
+
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    pq.load()
+    return dict(torch=torch, oracle=oracle, pq=pq, W=W, dev=torch.device("cuda:0"))
+
+
+def _dev(env, a):
+    return env["torch"].from_numpy(np.ascontiguousarray(a)).to(env["dev"])
+
+
+def _sync(env):
+    env["torch"].cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------ tables
+@pytest.mark.parametrize("cfg,over", [(1, {}), (3, {}), (4, dict(M=8, D=1024)), (2, dict(M=3, D=21))])
+def test_build_tables(env, cfg, over):
+    w = workload(cfg, **over)
+    cw = env["W"].codewords(w)
+    got = env["pq"].build_tables(_dev(env, cw))
+    _sync(env)
+    ref = env["oracle"].build_tables(cw)
+    got = got.cpu().numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-6, atol=0)
+    assert (got == ref).all()            # same fp64 operation order -> in fact identical
+    for m in range(w.M):
+        assert (np.diag(got[m]) == 0).all() and (got[m] == got[m].T).all()
+
+
+# ------------------------------------------------------------------------------------ assign
+def _check_assign(env, codes, centers, tables, **opts):
+    pq, oracle = env["pq"], env["oracle"]
+    for k, v in opts.items():
+        pq.set_option(k, v)
+    try:
+        a, d = pq.assign(_dev(env, codes), _dev(env, centers), _dev(env, tables))
+        _sync(env)
+    finally:
+        for k in opts:
+            pq.set_option(k, 0)
+    ra, rd = oracle.assign(codes, centers, tables)
+    np.testing.assert_array_equal(a.cpu().numpy(), ra)
+    np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+
+
+@pytest.mark.parametrize("M", [4, 8, 16, 32])
+@pytest.mark.parametrize("N,K", [(5003, 77), (1, 1), (513, 32), (2049, 33), (300, 1000)])
+def test_assign_tiled_matches_oracle(env, M, N, K):
+    """Several center tiles with a ragged last tile, several workgroups with a ragged tail."""
+    w = workload(1, M=M, D=32 * M, N=max(N, K), K=K, T=20)
+    W = env["W"]
+    codes_all = W.codes_numpy(w)
+    centers = codes_all[W.init_center_indices(w)].copy()
+    codes = codes_all[:N]
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2)
+    rng = np.random.default_rng(N + K + M)
+    _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=2)     # non-symmetric tables
+
+
+@pytest.mark.parametrize("M", [1, 3, 4, 6, 8])
+def test_assign_generic_matches_oracle(env, M):
+    rng = np.random.default_rng(M)
+    codes = rng.integers(0, 256, size=(3001, M), dtype=np.uint8)
+    centers = rng.integers(0, 256, size=(45, M), dtype=np.uint8)
+    _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=1)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_assign_every_compiled_shape(env, variant):
+    w = workload(1, N=9001, K=131, T=40)
+    W = env["W"]
+    codes = W.codes_numpy(w)
+    centers = codes[W.init_center_indices(w)].copy()
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+
+
+@pytest.mark.parametrize("M", [4, 8, 5])
+def test_assign_ties_go_to_lowest_index(env, M):
+    """Hamming tables: massive ties, in and across tiles and lanes."""
+    rng = np.random.default_rng(7)
+    tables = np.ones((M, 256, 256), np.float32)
+    for m in range(M):
+        np.fill_diagonal(tables[m], 0)
+    codes = rng.integers(0, 3, size=(4000, M), dtype=np.uint8)
+    centers = rng.integers(0, 3, size=(300, M), dtype=np.uint8)
+    _check_assign(env, codes, centers, tables)
+    _check_assign(env, codes, codes[:1500].copy(), tables)       # centers = codes -> distance 0, first holder
+
+
+def test_assign_degenerate_inputs(env):
+    pq, torch, dev = env["pq"], env["torch"], env["dev"]
+    rng = np.random.default_rng(8)
+    tables = rand_tables(rng, 4)
+    centers = rng.integers(0, 256, size=(10, 4), dtype=np.uint8)
+    # N = 0
+    a, d = pq.assign(torch.empty((0, 4), dtype=torch.uint8, device=dev), _dev(env, centers), _dev(env, tables))
+    assert a.numel() == 0
+    # infinities: a center at infinite distance is never chosen; all-infinite -> center 0
+    t2 = tables.copy()
+    t2[0, :, centers[3, 0]] = np.inf
+    codes = rng.integers(0, 256, size=(777, 4), dtype=np.uint8)
+    _check_assign(env, codes, centers, t2)
+    t3 = np.full_like(tables, np.inf)
+    _check_assign(env, codes, centers, t3)
+    # dist = NULL
+    a, d = pq.assign(_dev(env, codes), _dev(env, centers), _dev(env, tables), want_dist=False)
+    _sync(env)
+    assert d is None
+    np.testing.assert_array_equal(a.cpu().numpy(), env["oracle"].assign(codes, centers, tables)[0])
+
+
+# ------------------------------------------------------------------------------------ update
+@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000)])
+def test_update_matches_oracle(env, M, K, N):
+    rng = np.random.default_rng(M * K)
+    pq, oracle = env["pq"], env["oracle"]
+    for integer in (False, True):
+        tables = rand_tables(rng, M, integer=integer)
+        codes = rng.integers(0, 12, size=(N, M), dtype=np.uint8)
+        a = rng.integers(0, K - 1, size=N).astype(np.int32)           # last cluster stays empty
+        centers = rng.integers(0, 256, size=(K, M), dtype=np.uint8)
+        d_cent = _dev(env, centers)
+        _, hist, counts = pq.update(_dev(env, codes), _dev(env, a), _dev(env, tables), d_cent)
+        _sync(env)
+        rc, rh, rcnt = oracle.update(codes, a, tables, centers)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+        assert (rc[K - 1] == centers[K - 1]).all()
+        # hist / counts in the workspace
+        d_cent2 = _dev(env, centers)
+        pq.update(_dev(env, codes), _dev(env, a), _dev(env, tables), d_cent2, want_hist=False)
+        _sync(env)
+        np.testing.assert_array_equal(d_cent2.cpu().numpy(), rc)
+
+
+def test_update_empty_input_and_big_counts(env):
+    pq, oracle, torch, dev = env["pq"], env["oracle"], env["torch"], env["dev"]
+    rng = np.random.default_rng(9)
+    M, K = 4, 5
+    tables = rand_tables(rng, M)
+    centers = rng.integers(0, 256, size=(K, M), dtype=np.uint8)
+    d_cent = _dev(env, centers)
+    _, hist, counts = pq.update(torch.empty((0, M), dtype=torch.uint8, device=dev),
+                                torch.empty(0, dtype=torch.int32, device=dev), _dev(env, tables), d_cent)
+    _sync(env)
+    assert u32(hist).sum() == 0 and u32(counts).sum() == 0
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), centers)
+    # one heavy cluster: counts beyond 2**24 exercise the int -> float rounding of the vote
+    N = (1 << 24) + 12345
+    codes = np.zeros((N, M), np.uint8)
+    codes[: N // 3] = 7
+    codes[N // 3:, 1] = 200
+    a = np.zeros(N, np.int32)
+    a[-5:] = 3
+    d_cent = _dev(env, centers)
+    _, hist, counts = pq.update(_dev(env, codes), _dev(env, a), _dev(env, tables), d_cent)
+    _sync(env)
+    rc, rh, rcnt = oracle.update(codes, a, tables, centers)
+    np.testing.assert_array_equal(u32(hist), rh)
+    np.testing.assert_array_equal(u32(counts), rcnt)
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
+# ------------------------------------------------------------------------------------ Alg. 1 on the configs
+def _run_config_full(env, cfg, iters, **over):
+    """Every iteration compared in full: assign, dist, hist, counts, centers."""
+    pq, oracle, W = env["pq"], env["oracle"], env["W"]
+    w = workload(cfg, **over)
+    cw = W.codewords(w)
+    codes = W.codes_numpy(w)
+    cent = codes[W.init_center_indices(w)].copy()
+    tables_d = pq.build_tables(_dev(env, cw))
+    _sync(env)
+    tables = tables_d.cpu().numpy()
+    np.testing.assert_allclose(tables, oracle.build_tables(cw), rtol=1e-6, atol=0)
+    d_codes, d_cent = _dev(env, codes), _dev(env, cent)
+    empties = 0
+    for it in range(iters):
+        a, d = pq.assign(d_codes, d_cent, tables_d)
+        _, hist, counts = pq.update(d_codes, a, tables_d, d_cent)
+        _sync(env)
+        ra, rd = oracle.assign(codes, cent, tables)
+        cent, rh, rcnt = oracle.update(codes, ra, tables, cent)
+        np.testing.assert_array_equal(a.cpu().numpy(), ra)
+        np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), cent)
+        empties += int((rcnt == 0).sum())
+        progress(f"config {cfg} iteration {it + 1}/{iters} bit-exact")
+    # the same through pqkm_fit
+    cent0 = codes[W.init_center_indices(w)].copy()
+    d_cent = _dev(env, cent0)
+    _, fa = pq.fit(d_codes, tables_d, d_cent, iters)
+    _sync(env)
+    rc, ra, _, _ = oracle.fit(codes, tables, cent0, iters)
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+    np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+    return empties
+
+
+def test_config1_tiny_all_iterations(env):
+    empties = _run_config_full(env, 1, workload(1).iters)
+    assert empties > 0          # duplicate initial centers guarantee empty clusters here
+
+
+def test_config2_sift32_all_iterations(env):
+    _run_config_full(env, 2, workload(2).iters)
+
+
+def _run_config_sampled(env, cfg, n_sample, iters=1):
+    """Full-size run in the launch configuration the benchmark uses.  The assignment is checked
+    on a seeded sample of codes against all K centers; histogram, counts and vote are checked in
+    full by giving the GPU's assignment to the oracle."""
+    pq, oracle, W, torch, dev = env["pq"], env["oracle"], env["W"], env["torch"], env["dev"]
+    w = workload(cfg)
+    cw = W.codewords(w)
+    tables_d = pq.build_tables(_dev(env, cw))
+    _sync(env)
+    tables = tables_d.cpu().numpy()
+    progress(f"config {cfg}: generating {w.N} codes on the GPU")
+    d_codes = W.codes_torch(w, dev)
+    init = W.init_center_indices(w)
+    cent = W.codes_at(w, init)
+    np.testing.assert_array_equal(d_codes[torch.from_numpy(init).to(dev)].cpu().numpy(), cent)
+    rng = np.random.default_rng(w.seed)
+    sample = np.sort(rng.choice(w.N, size=n_sample, replace=False))
+    sample[0], sample[-1] = 0, w.N - 1
+    s_codes = W.codes_at(w, sample)
+    np.testing.assert_array_equal(d_codes[torch.from_numpy(sample).to(dev)].cpu().numpy(), s_codes)
+    d_cent = _dev(env, cent)
+    ws = torch.empty(pq.workspace_bytes(w.N, w.M, w.K), dtype=torch.uint8, device=dev)
+    a = torch.empty(w.N, dtype=torch.int32, device=dev)
+    d = torch.empty(w.N, dtype=torch.float32, device=dev)
+    hist = torch.empty((w.K, w.M, 256), dtype=torch.int32, device=dev)
+    counts = torch.empty(w.K, dtype=torch.int32, device=dev)
+    for it in range(iters):
+        progress(f"config {cfg}: iteration {it + 1} assign on the GPU")
+        pq.assign(d_codes, d_cent, tables_d, assign=a, dist=d, workspace=ws)
+        _sync(env)
+        progress(f"config {cfg}: oracle on {n_sample} sampled codes x {w.K} centers")
+        ra, rd = oracle.assign(s_codes, cent, tables)
+        idx = torch.from_numpy(sample).to(dev)
+        np.testing.assert_array_equal(a[idx].cpu().numpy(), ra)
+        np.testing.assert_array_equal(d[idx].cpu().numpy().view(np.uint32), rd.view(np.uint32))
+        assert int(a.min()) >= 0 and int(a.max()) < w.K
+        progress(f"config {cfg}: update on the GPU")
+        pq.update(d_codes, a, tables_d, d_cent, hist=hist, counts=counts, workspace=ws)
+        _sync(env)
+        progress(f"config {cfg}: oracle histogram + vote in full")
+        h_codes = d_codes.cpu().numpy()
+        h_a = a.cpu().numpy()
+        cent, rh, rcnt = oracle.update(h_codes, h_a, tables, cent)
+        del h_codes, h_a
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), cent)
+        progress(f"config {cfg}: iteration {it + 1} bit-exact (assign sampled, update full)")
+
+
+def test_config3_sift64_sampled(env):
+    _run_config_sampled(env, 3, 100_000, iters=2)
+
+
+def test_config4_cnn_sampled(env):
+    _run_config_sampled(env, 4, 20_000, iters=1)
+
+
+def test_config5_billion_sampled(env):
+    _run_config_sampled(env, 5, 100_000, iters=1)
