@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the PQk-means iteration on one MI355X.
+
+A "step" is one whole iteration of Alg. 1 (assignment by linear scan, Eq. 5, then the
+sparse-voting update, Eq. 7-8) over the synthetic SIFT-like 32-bit workload (configuration 2:
+N = 1e6 codes, M = 4, K = 1e3 centers), issued through the C ABI (pqkm_fit with one iteration).
+Inputs are generated on the GPU and are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is code-center SDC evaluations per second over the whole step
+(N*K / time per iteration, update included); `assign_evals_per_s` counts the scan kernel alone.
+`roofline` is for the dominant kernel, the LDS-tiled assignment scan: achieved = N*K*M table
+lookups of 4 bytes per launch / the kernel's average duration (HIP events recorded by the
+library on the stream the kernel runs on), against the LDS gather peak of the chip
+(256 CUs x 2.4 GHz x 256 B/clk).  `cpu_baseline` is the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+LDS_PEAK_GBS = 256 * 2.4e9 * 256 / 1e9          # 157286 GB/s: 256 CUs x 2.4 GHz x 256 B/clk (ds_read_b128)
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration (1-5); 2 is the benchmark's")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1709_03708_amd as pq
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    pq.load()                                           # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    w = W.CONFIGS[args.config]
+    N, M, K = w.N, w.M, w.K
+
+    cw = W.codewords(w)
+    tables = pq.build_tables(torch.from_numpy(cw).to(dev))
+    codes = W.codes_torch(w, dev)
+    init_idx = W.init_center_indices(w)
+    centers0 = torch.from_numpy(W.codes_at(w, init_idx)).to(dev)
+    centers = centers0.clone()
+    assign = torch.empty(N, dtype=torch.int32, device=dev)
+    ws = torch.empty(pq.workspace_bytes(N, M, K), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    pq.set_option("profile", 1)
+    for _ in range(args.warmup):
+        pq.fit(codes, tables, centers, 1, assign=assign, workspace=ws)
+    torch.cuda.synchronize()
+    pq.profile_read()                                   # discard the warm-up launches
+
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pq.fit(codes, tables, centers, 1, assign=assign, workspace=ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    scan_ms_total, scan_launches = pq.profile_read()
+    pq.set_option("profile", 0)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    evals = float(N) * K
+    value = evals / (ms_per_step * 1e-3)
+    scan_ms = scan_ms_total / max(scan_launches, 1)
+    launches_per_step = scan_launches / args.steps
+    lookups_per_launch = evals * M / launches_per_step
+    achieved_gbs = lookups_per_launch * 4 / (scan_ms * 1e-3) / 1e9
+
+    # HBM traffic of the scan kernel, from the committed rocprofv3 --pmc summary if it covers this workload
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get("scan_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "code-center SDC evaluations/sec in assignment (N*K/s); seconds per PQk-means iter",
+        "value": value,
+        "unit": "SDC evaluations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "sec_per_iter": ms_per_step * 1e-3,
+        "assign_evals_per_s": evals * args.steps / (scan_ms_total * 1e-3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config} ({w.name}): N={N} uint8 codes, M={M}, K={K}, D={w.D}",
+                   "N": N, "M": M, "K": K, "iterations_timed": args.steps},
+        "roofline": {"bound": "lds", "kernel": "assign_scan (LDS-tiled linear scan, Eq. 5)",
+                     "achieved": achieved_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved_gbs / LDS_PEAK_GBS, "traffic": traffic,
+                     "avg_kernel_ms": scan_ms, "launches": scan_launches,
+                     "lookups_per_s": lookups_per_launch / (scan_ms * 1e-3),
+                     "hbm_algorithmic_gbs": (N * M + 4 * N) / (scan_ms * 1e-3) / 1e9,
+                     "hbm_peak_gbs": HBM_PEAK_GBS},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        h_codes = codes.cpu().numpy()
+        h_tables = tables.cpu().numpy()
+        cent = centers0.cpu().numpy()
+        cores = oracle.max_threads()
+        # bounded sample: first n_sub codes, sized for about 10 s of CPU work at ~1e8 evaluations/s/thread
+        n_sub = int(min(N, max(10_000, 10.0 * 1e8 * cores / K)))
+        reps, t_cpu = 0, 0.0
+        c0 = time.perf_counter()
+        while True:
+            a, _ = oracle.assign(h_codes[:n_sub], cent, h_tables, want_dist=False)
+            cent2, _, _ = oracle.update(h_codes[:n_sub], a, h_tables, cent)
+            reps += 1
+            t_cpu = time.perf_counter() - c0
+            if t_cpu >= 10.0 or reps >= 200:
+                break
+        out["cpu_baseline"] = {"value": float(n_sub) * K * reps / t_cpu, "unit": "SDC evaluations/s",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"{reps} oracle iterations (assign + update) over the first {n_sub} codes "
+                                         f"x all {K} centers, {t_cpu:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -95,6 +95,26 @@ void launch_scan(const uint8_t* codes, int64_t N, const float4* img, int ntiles,
                        img, ntiles, assign, dist);
 }
 
+template <int R, int THREADS, bool PF>
+void launch_scan4(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                  hipStream_t st)
+{
+    constexpr int C = (THREADS / 8) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4_kernel<R, THREADS, PF>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, img,
+                       ntiles, assign, dist);
+}
+
+template <int R, int THREADS, bool PF>
+void launch_scan4x2(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                    hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4x2_kernel<R, THREADS, PF>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
+                       img, ntiles, assign, dist);
+}
+
 template <int M>
 void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                    float* dist, hipStream_t st);
@@ -112,7 +132,28 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 6: launch_scan<4, 12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 7: launch_scan<4, 32, 256, false>(codes, N, img, ntiles, assign, dist, st); break;
         case 8: launch_scan<4, 32, 256, true>(codes, N, img, ntiles, assign, dist, st); break;
-        default: launch_scan<4, 16, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 10: launch_scan4<32, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 11: launch_scan4<32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 12: launch_scan4<24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 13: launch_scan4<16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 14: launch_scan4<16, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 15: launch_scan4<16, 1024, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 16: launch_scan4<28, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 17: launch_scan4<20, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 18: launch_scan4<8, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 19: launch_scan4<12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 20: launch_scan4x2<32, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 21: launch_scan4x2<24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 22: launch_scan4x2<16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 23: launch_scan4x2<12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 24: launch_scan4x2<8, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 25: launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 26: launch_scan4x2<32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        default:
+            // few tiles: the per-workgroup prologue/epilogue matters, more waves hide it better
+            if (ntiles <= 64) launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st);
+            else launch_scan4x2<32, 512, true>(codes, N, img, ntiles, assign, dist, st);
+            break;
     }
 }
 template <>

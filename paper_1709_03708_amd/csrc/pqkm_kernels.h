@@ -249,6 +249,375 @@ __global__ __launch_bounds__(THREADS) void assign_scan_kernel(const uint8_t* __r
 }
 
 // ---------------------------------------------------------------------------------------------
+// M = 4 specialisation of the LDS-tiled scan (32/64-bit SIFT-like codes are the paper's main
+// workload, Tab. 3 and Tab. 5).  Same decomposition as above (TK = 32 centers per tile, 8 lanes
+// per slot, one ds_read_b128 per lane, code and subspace), tuned for the register file:
+//
+//  * per code and lane only 4 registers persist: two words of packed, pre-scaled LDS row
+//    offsets (four 16-bit fields (x_m*128 + 16q)/16, the two upper subspaces biased by 64 KB so
+//    that the remaining plane offset fits the 16-bit DS immediate; one SDWA shift unpacks a
+//    field), the running minimum and the index of the TILE in which it last improved;
+//  * the minimum is tracked with two v_min3 per 4 centers and one compare; which of the lane's
+//    4 centers of that tile attains it is recovered once, after the last tile, by re-reading
+//    those 4x4 entries from the tile image in global memory (same bits, same sum order) and
+//    taking the first equal one -- the same center a sequential strict "<" scan would keep;
+//  * LDS reads of code r+1 are issued before the sums of code r are formed;
+//  * the next tile is prefetched from global memory into registers while the current one is
+//    being scanned, so only the LDS write of the fill is exposed between two barriers.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sdwa_shl_word0(uint32_t sh, uint32_t v)
+{
+    uint32_t r;
+    asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+        : "=v"(r) : "v"(sh), "v"(v));
+    return r;
+}
+__device__ __forceinline__ uint32_t sdwa_shl_word1(uint32_t sh, uint32_t v)
+{
+    uint32_t r;
+    asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1"
+        : "=v"(r) : "v"(sh), "v"(v));
+    return r;
+}
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+struct Quad4 { float4 v0, v1, v2, v3; };
+
+template <int R, int THREADS, bool PREFETCH>
+__global__ __launch_bounds__(THREADS) void assign_scan4_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                               const float4* __restrict__ img, int ntiles,
+                                                               int32_t* __restrict__ assign,
+                                                               float* __restrict__ dist)
+{
+    constexpr int LPS = 8, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr int PLANE = 32768;            // bytes per subspace plane: 256 rows of 128 bytes
+    static_assert(R % 2 == 0, "the read pipeline handles codes in pairs");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    uint32_t pa[R], pb[R];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        uint32_t f0 = ((pk & 255u) << 3) | q;
+        uint32_t f1 = (((pk >> 8) & 255u) << 3) | q;
+        uint32_t f2 = ((((pk >> 16) & 255u) << 3) | q) + 4096u;
+        uint32_t f3 = (((pk >> 24) << 3) | q) + 4096u;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    // tile fill addressing: one buffer descriptor per tile (wave-uniform, in SGPRs), a scalar
+    // offset per 16-byte-per-thread slab and a single 32-bit lane offset
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+    if (PREFETCH) {
+#pragma unroll
+        for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+    }
+
+    auto issue = [&](int r) -> Quad4 {
+        Quad4 u;
+        u.v0 = lds_read16(tb, sdwa_shl_word0(four, pa[r]));
+        u.v1 = lds_read16(tb, sdwa_shl_word1(four, pa[r]) + PLANE);
+        u.v2 = lds_read16(tb, sdwa_shl_word0(four, pb[r]));
+        u.v3 = lds_read16(tb, sdwa_shl_word1(four, pb[r]) + PLANE);
+        return u;
+    };
+    auto consume = [&](const Quad4& u, int r, int t) {
+        float sx = u.v0.x + u.v1.x, sy = u.v0.y + u.v1.y, sz = u.v0.z + u.v1.z, sw = u.v0.w + u.v1.w;
+        sx = sx + u.v2.x; sy = sy + u.v2.y; sz = sz + u.v2.z; sw = sw + u.v2.w;
+        sx = sx + u.v3.x; sy = sy + u.v3.y; sz = sz + u.v3.z; sw = sw + u.v3.w;
+        float m4 = __builtin_fminf(__builtin_fminf(sx, sy), __builtin_fminf(sz, sw));
+        tix[r] = (m4 < best[r]) ? t : tix[r];
+        best[r] = __builtin_fminf(best[r], m4);
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();                       // everyone is done reading the previous tile
+        if (PREFETCH) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        } else {
+            v4f tmp[NF];
+#pragma unroll
+            for (int i = 0; i < NF; ++i) tmp[i] = gload(t, i);
+#pragma unroll
+            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = tmp[i];
+        }
+        __syncthreads();
+        if (PREFETCH) {
+            // the last iteration re-reads its own tile: a harmless, unconditional load
+            const int tn = t + 1 < ntiles ? t + 1 : t;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
+        }
+        Quad4 ua = issue(0);
+#pragma unroll
+        for (int r = 0; r < R; r += 2) {
+            Quad4 ub = issue(r + 1);
+            consume(ua, r, t);
+            if (r + 2 < R) ua = issue(r + 2);
+            consume(ub, r + 1, t);
+        }
+    }
+
+    // recover the center index inside the winning tile, then merge the 8 lanes of the slot.
+    // Codes are handled four at a time so that their 16 global loads are in flight together.
+    constexpr int G = 4;
+    static_assert(R % G == 0, "the epilogue handles codes in groups of four");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][4];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            // r0 is a run-time value here: select this group's state without dynamic register indexing
+            uint32_t a = 0, b2 = 0;
+            int tx = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tx = tix[r]; }
+            const char* gbase = reinterpret_cast<const char*>(img + (size_t)(tx < 0 ? 0 : tx) * TILE_F4);
+            w[g][0] = *reinterpret_cast<const v4f*>(gbase + ((a & 0xffffu) << 4));
+            w[g][1] = *reinterpret_cast<const v4f*>(gbase + ((a >> 16) << 4) + PLANE);
+            w[g][2] = *reinterpret_cast<const v4f*>(gbase + ((b2 & 0xffffu) << 4));
+            w[g][3] = *reinterpret_cast<const v4f*>(gbase + ((b2 >> 16) << 4) + PLANE);
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int tx = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { b = best[r]; tx = tix[r]; }
+            int bi = IDX_NONE;
+            v4f sv = w[g][0] + w[g][1];
+            sv = sv + w[g][2];
+            sv = sv + w[g][3];
+            if (tx >= 0) {
+                const int kb = tx * TK + q * 4;
+                const float bb = b;
+                if (sv.w == bb) { bi = kb + 3; b = sv.w; }
+                if (sv.z == bb) { bi = kb + 2; b = sv.z; }
+                if (sv.y == bb) { bi = kb + 1; b = sv.y; }
+                if (sv.x == bb) { bi = kb; b = sv.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                assign[n] = (bi == IDX_NONE) ? 0 : bi;
+                if (dist) dist[n] = b;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 4 scan with 4 lanes per slot: each lane owns 8 of the tile's 32 centers (two 16-byte reads
+// per subspace, the two halves of the 128-byte row), which halves the number of lanes that must
+// replicate a code's state, so a workgroup holds twice as many codes per tile fill (C = 128*R at
+// 512 threads).  Slots of odd index read the upper half-row first, which spreads the four slots
+// of a 16-lane LDS access group over the banks.  Because only the minimum over the lane's 8
+// centers and the tile index are tracked, the order in which a lane meets its centers inside a
+// tile does not matter; the epilogue re-derives the winner inside the winning tile in ascending
+// center order.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS, bool PREFETCH>
+__global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                 const float4* __restrict__ img, int ntiles,
+                                                                 int32_t* __restrict__ assign,
+                                                                 float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr int PLANE = 32768;
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const uint32_t par = (uint32_t)c & 1u;         // odd slots start with the upper half-row
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    uint32_t pa[R], pb[R];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        const uint32_t lo = (par << 2) | (uint32_t)q;               // (par*64 + q*16) / 16
+        uint32_t f0 = ((pk & 255u) << 3) | lo;
+        uint32_t f1 = (((pk >> 8) & 255u) << 3) | lo;
+        uint32_t f2 = ((((pk >> 16) & 255u) << 3) | lo) + 4096u;
+        uint32_t f3 = (((pk >> 24) << 3) | lo) + 4096u;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+    if (PREFETCH) {
+#pragma unroll
+        for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+    }
+
+    // one unit of work = (code r, half h): 4 reads, one per subspace
+    auto issue = [&](int r, int h) -> Quad4 {
+        Quad4 u;
+        const uint32_t flip = h ? 64u : 0u;
+        u.v0 = lds_read16(tb, sdwa_shl_word0(four, pa[r]) ^ flip);
+        u.v1 = lds_read16(tb, (sdwa_shl_word1(four, pa[r]) ^ flip) + PLANE);
+        u.v2 = lds_read16(tb, sdwa_shl_word0(four, pb[r]) ^ flip);
+        u.v3 = lds_read16(tb, (sdwa_shl_word1(four, pb[r]) ^ flip) + PLANE);
+        return u;
+    };
+    auto min4 = [&](const Quad4& u) -> float {
+        float sx = u.v0.x + u.v1.x, sy = u.v0.y + u.v1.y, sz = u.v0.z + u.v1.z, sw = u.v0.w + u.v1.w;
+        sx = sx + u.v2.x; sy = sy + u.v2.y; sz = sz + u.v2.z; sw = sw + u.v2.w;
+        sx = sx + u.v3.x; sy = sy + u.v3.y; sz = sz + u.v3.z; sw = sw + u.v3.w;
+        return __builtin_fminf(__builtin_fminf(sx, sy), __builtin_fminf(sz, sw));
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+        if (PREFETCH) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        } else {
+            v4f tmp[NF];
+#pragma unroll
+            for (int i = 0; i < NF; ++i) tmp[i] = gload(t, i);
+#pragma unroll
+            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = tmp[i];
+        }
+        __syncthreads();
+        if (PREFETCH) {
+            const int tn = t + 1 < ntiles ? t + 1 : t;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
+        }
+        Quad4 ua = issue(0, 0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            Quad4 ub = issue(r, 1);
+            float m8 = min4(ua);
+            if (r + 1 < R) ua = issue(r + 1, 0);
+            m8 = __builtin_fminf(m8, min4(ub));
+            tix[r] = (m8 < best[r]) ? t : tix[r];
+            best[r] = __builtin_fminf(best[r], m8);
+        }
+    }
+
+    constexpr int G = THREADS > 512 ? 1 : 4;
+    static_assert(R % G == 0, "the epilogue handles codes in groups");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint32_t a = 0, b2 = 0;
+            int tx = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tx = tix[r]; }
+            const char* gbase = reinterpret_cast<const char*>(img + (size_t)(tx < 0 ? 0 : tx) * TILE_F4);
+            const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + PLANE;
+            const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + PLANE;
+            // w[g][0..3]: the lower half-row (centers 4q..4q+3), w[g][4..7]: the upper one (16+4q..)
+            const uint32_t lowsel = par ? 64u : 0u;     // this lane's stored offsets point at half `par`
+            w[g][0] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel));
+            w[g][1] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel));
+            w[g][2] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel));
+            w[g][3] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel));
+            w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel ^ 64u));
+            w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel ^ 64u));
+            w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel ^ 64u));
+            w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel ^ 64u));
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int tx = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { b = best[r]; tx = tix[r]; }
+            int bi = IDX_NONE;
+            v4f lo = w[g][0] + w[g][1];
+            lo = lo + w[g][2];
+            lo = lo + w[g][3];
+            v4f hi = w[g][4] + w[g][5];
+            hi = hi + w[g][6];
+            hi = hi + w[g][7];
+            if (tx >= 0) {
+                const int kb = tx * TK + q * 4;
+                const float bb = b;
+                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
+                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
+                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
+                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
+                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
+                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
+                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
+                if (lo.x == bb) { bi = kb; b = lo.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                assign[n] = (bi == IDX_NONE) ? 0 : bi;
+                if (dist) dist[n] = b;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Zero fill (a kernel, not a memset node, so that callers may capture the calls in a graph).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)
