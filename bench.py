@@ -35,6 +35,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload configuration (1-5); 2 is the benchmark's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device copy of 1 GiB (5 times): the known-size kernel against which "
+                         "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -51,6 +54,14 @@ def main() -> int:
         return 2
     pq.load()                                           # fails loudly if the HIP library is missing
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "copies": 5}))
+        return 0
     w = W.CONFIGS[args.config]
     N, M, K = w.N, w.M, w.K
 

@@ -122,6 +122,8 @@ pqkm_status pqkm_fit(const uint8_t *codes, int64_t N, int32_t M, const float *ta
  *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
  *   "scan_variant"       0 = default launch shape of the LDS-tiled scan, 1..64 =
  *                        one specific compiled shape (for tuning sweeps)
+ *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
+ *                        per code and subspace, 2 = force the LDS-privatised histogram
  *   "launch_codes_log2"  the scan is issued in launches of 2^value codes (default 26)
  *   "profile"            1 = bracket every scan-kernel launch with a pair of HIP
  *                        events on the caller's stream (events are created on

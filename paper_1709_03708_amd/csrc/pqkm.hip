@@ -18,6 +18,7 @@ using namespace pqkm;
 struct Options {
     int assign_kernel = 0;   // 0 auto, 1 generic, 2 tiled
     int scan_variant = 0;    // 0 auto, else a specific instantiation (tuning)
+    int hist_kernel = 0;     // 0 auto, 1 global atomics, 2 LDS-privatised owner path
     int profile = 0;         // bracket scan kernels with events
     int64_t launch_codes = (int64_t)1 << 26;   // codes per scan launch
 };
@@ -32,10 +33,26 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
-    size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, total;
+    size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, total;
 };
 
-Carve carve(int64_t /*N*/, int M, int K)
+// Shape of the LDS-privatised histogram pass: KT clusters per workgroup, `groups` cluster groups, S code slices.
+struct HistPlan { int KT; int64_t groups; int S; bool cheap; };
+
+HistPlan hist_plan(int64_t N, int M, int K)
+{
+    HistPlan p{};
+    p.KT = (HIST_LDS_WORDS / L) / M;                       // 128 KB of LDS / (M KB per cluster)
+    if (p.KT < 1) return p;
+    p.groups = ((int64_t)K + p.KT - 1) / p.KT;
+    p.S = 1;
+    while (p.groups * p.S < 256 && p.S < 8 && N / (2 * p.S) >= 8192) p.S *= 2;
+    // every cluster group streams the whole assignment array: worth it while that stays small
+    p.cheap = (double)p.groups * (double)N * 4.0 <= 4.0e9;
+    return p;
+}
+
+Carve carve(int64_t N, int M, int K)
 {
     Carve c{};
     size_t off = 0;
@@ -52,6 +69,10 @@ Carve carve(int64_t /*N*/, int M, int K)
     c.counts_off = off;
     c.counts_bytes = (size_t)K * sizeof(uint32_t);
     off += align256(c.counts_bytes);
+    c.parts_off = off;
+    HistPlan hp = hist_plan(N, M, K);
+    c.parts_bytes = (hp.KT >= 1 && hp.S > 1) ? (size_t)hp.S * align256(c.hist_bytes) : 0;
+    off += c.parts_bytes;
     c.total = off;
     return c;
 }
@@ -149,6 +170,9 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 24: launch_scan4x2<8, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 25: launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 26: launch_scan4x2<32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 27: launch_scan4x2<28, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 28: launch_scan4x2<14, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
+        case 29: launch_scan4x2<20, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
         default:
             // few tiles: the per-workgroup prologue/epilogue matters, more waves hide it better
             if (ntiles <= 64) launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st);
@@ -241,21 +265,43 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     Carve c = carve(N, M, K);
     if (!hist) hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.hist_off);
     if (!counts) counts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.counts_off);
-    int64_t nh = (int64_t)K * M * L;
-    unsigned zb = (unsigned)((nh + 255) / 256 < 65536 ? (nh + 255) / 256 : 65536);
-    hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, hist, nh);
-    hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, counts, (int64_t)K);
-    if (N > 0) {
+    const int64_t nh = (int64_t)K * M * L;
+    auto zero_hist = [&]() {
+        unsigned zb = (unsigned)((nh + 255) / 256 < 65536 ? (nh + 255) / 256 : 65536);
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, hist, nh);
+    };
+    // Owner path (LDS-privatised, no global atomics) while streaming the assignment array once per cluster
+    // group is cheap; otherwise one global atomic per code and subspace into a zeroed histogram.
+    const HistPlan hp = hist_plan(N, M, K);
+    int force;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        force = g_opt.hist_kernel;
+    }
+    const bool owner = hp.KT >= 1 && force != 1 && (force == 2 || hp.cheap);
+    int S = 1;
+    size_t part_stride = 0;
+    uint32_t* parts = hist;
+    if (owner) {
+        S = hp.S;
+        if (S > 1) {
+            parts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.parts_off);
+            part_stride = align256(c.hist_bytes) / sizeof(uint32_t);
+        }
+        hipLaunchKernelGGL(histogram_owner_kernel, dim3((unsigned)(hp.groups * S)), dim3(1024), 0, st, codes, N, M,
+                           assign, K, hp.KT, S, parts, part_stride);
+    } else {
+        zero_hist();
         const int64_t per = (int64_t)1 << 30;
         for (int64_t n0 = 0; n0 < N; n0 += per) {
             int64_t cnt = N - n0 < per ? N - n0 : per;
-            hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st,
-                               codes + n0 * M, cnt, M, assign + n0, K, hist, counts);
+            hipLaunchKernelGGL(histogram_atomic_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st,
+                               codes + n0 * M, cnt, M, assign + n0, K, hist);
         }
     }
     int64_t pairs = (int64_t)K * M;
-    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st, hist, counts, K, M, tables,
-                       centers);
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st, hist, parts, S, part_stride,
+                       counts, K, M, tables, centers);
     return launched();
 }
 
@@ -344,6 +390,9 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
     } else if (strcmp(name, "scan_variant") == 0) {
         if (value < 0 || value > 64) return PQKM_ERR_SHAPE;
         g_opt.scan_variant = value;
+    } else if (strcmp(name, "hist_kernel") == 0) {
+        if (value < 0 || value > 2) return PQKM_ERR_SHAPE;
+        g_opt.hist_kernel = value;
     } else if (strcmp(name, "profile") == 0) {
         if (value < 0 || value > 1) return PQKM_ERR_SHAPE;
         g_opt.profile = value;

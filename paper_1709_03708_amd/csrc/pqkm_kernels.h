@@ -503,14 +503,24 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
         for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
     }
 
-    // one unit of work = (code r, half h): 4 reads, one per subspace
-    auto issue = [&](int r, int h) -> Quad4 {
+    // one unit of work = (code r, half h): 4 reads, one per subspace.  The four row offsets are
+    // unpacked once per code; the second half-row is the first one with bit 6 flipped.
+    struct Addr4 { uint32_t a0, a1, a2, a3; };
+    auto unpack = [&](int r) -> Addr4 {
+        Addr4 a;
+        a.a0 = sdwa_shl_word0(four, pa[r]);
+        a.a1 = sdwa_shl_word1(four, pa[r]);
+        a.a2 = sdwa_shl_word0(four, pb[r]);
+        a.a3 = sdwa_shl_word1(four, pb[r]);
+        return a;
+    };
+    auto issue = [&](const Addr4& a, int h) -> Quad4 {
         Quad4 u;
         const uint32_t flip = h ? 64u : 0u;
-        u.v0 = lds_read16(tb, sdwa_shl_word0(four, pa[r]) ^ flip);
-        u.v1 = lds_read16(tb, (sdwa_shl_word1(four, pa[r]) ^ flip) + PLANE);
-        u.v2 = lds_read16(tb, sdwa_shl_word0(four, pb[r]) ^ flip);
-        u.v3 = lds_read16(tb, (sdwa_shl_word1(four, pb[r]) ^ flip) + PLANE);
+        u.v0 = lds_read16(tb, a.a0 ^ flip);
+        u.v1 = lds_read16(tb, (a.a1 ^ flip) + PLANE);
+        u.v2 = lds_read16(tb, a.a2 ^ flip);
+        u.v3 = lds_read16(tb, (a.a3 ^ flip) + PLANE);
         return u;
     };
     auto min4 = [&](const Quad4& u) -> float {
@@ -538,12 +548,16 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
 #pragma unroll
             for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
         }
-        Quad4 ua = issue(0, 0);
+        Addr4 ad = unpack(0);
+        Quad4 ua = issue(ad, 0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            Quad4 ub = issue(r, 1);
+            Quad4 ub = issue(ad, 1);
             float m8 = min4(ua);
-            if (r + 1 < R) ua = issue(r + 1, 0);
+            if (r + 1 < R) {
+                ad = unpack(r + 1);
+                ua = issue(ad, 0);
+            }
             m8 = __builtin_fminf(m8, min4(ub));
             tix[r] = (m8 < best[r]) ? t : tix[r];
             best[r] = __builtin_fminf(best[r], m8);
@@ -628,21 +642,22 @@ __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p,
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 7: hist[k][m][j] += 1 for every code n with assign[n] = k and codes[n][m] = j; counts[k].
-// Integer atomics: exact and independent of order.  One lane per code.
+// Eq. 7, atomic path: hist[k][m][j] += 1 for every code n with assign[n] = k, codes[n][m] = j.
+// Integer atomics: exact and independent of order.  One lane per code.  Used when the number of
+// centers is too large for the owner path below; hist must be zero on entry.  Cluster sizes are
+// not counted here: the vote derives them from the histogram (sum over the bins of a subspace).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void histogram_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
-                                                        const int32_t* __restrict__ assign, int K,
-                                                        uint32_t* __restrict__ hist, uint32_t* __restrict__ counts)
+__global__ __launch_bounds__(256) void histogram_atomic_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
+                                                               const int32_t* __restrict__ assign, int K,
+                                                               uint32_t* __restrict__ hist)
 {
     int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     int k = assign[n];
     if ((unsigned)k >= (unsigned)K) return;
-    atomicAdd(&counts[k], 1u);
     const uint8_t* x = codes + n * M;
     uint32_t* h = hist + (size_t)k * M * L;
-    if ((M & 3) == 0) {
+    if ((M & 3) == 0 && ((uintptr_t)codes & 3) == 0) {
         const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
         for (int w = 0; w < M / 4; ++w) {
             uint32_t p = xw[w];
@@ -657,30 +672,161 @@ __global__ __launch_bounds__(256) void histogram_kernel(const uint8_t* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
+// Eq. 7, owner path: LDS-privatised histograms.  Workgroup (g, s) owns the KT consecutive
+// clusters k0 = g*KT .. and the s-th of S equal slices of the codes; it streams its slice of
+// `assign` (coalesced, several loads in flight per lane), and for the few codes that fall in its
+// cluster range it increments a private copy of their M histograms in LDS (KT*M*1 KB <= 128 KB).
+// The private copy is stored whole (zeros included, so nothing needs clearing): with S = 1 it IS
+// the result; with S > 1 slice s goes to its own partial array out + s*part_stride, and the
+// vote kernel adds the S partials when it loads a histogram.  No global atomics at all -- they
+// resolve outside the XCD-private L2 on this chip and are slow on hot bins.
+// ---------------------------------------------------------------------------------------------
+constexpr int HIST_LDS_WORDS = 32768;   // 128 KB
+
+__global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
+                                                               const int32_t* __restrict__ assign, int K, int KT,
+                                                               int S, uint32_t* __restrict__ hist,
+                                                               size_t part_stride)
+{
+    __shared__ uint32_t lh[HIST_LDS_WORDS];
+    const int tid = threadIdx.x;
+    const int g = blockIdx.x / S, s = blockIdx.x % S;
+    const int k0 = g * KT;
+    const int kt = (K - k0 < KT) ? K - k0 : KT;
+    const int words = kt * M * L;
+    for (int i = tid; i < words; i += 1024) lh[i] = 0u;
+    __syncthreads();
+
+    // slice [lo, hi) of the codes, cut at multiples of 4 so that 16-byte loads stay aligned
+    const int64_t lo = (N * s / S) & ~(int64_t)3;
+    const int64_t hi = (s + 1 == S) ? N : ((N * (s + 1) / S) & ~(int64_t)3);
+    const bool wide = (M & 3) == 0 && ((uintptr_t)codes & 3) == 0;
+    auto add_code = [&](int kk, int64_t n) {
+        uint32_t* h = lh + (size_t)kk * M * L;
+        const uint8_t* x = codes + n * M;
+        if (wide) {
+            const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
+            for (int w = 0; w < M / 4; ++w) {
+                uint32_t p = xw[w];
+                atomicAdd(&h[(4 * w + 0) * L + (p & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 1) * L + ((p >> 8) & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 2) * L + ((p >> 16) & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 3) * L + (p >> 24)], 1u);
+            }
+        } else {
+            for (int m = 0; m < M; ++m) atomicAdd(&h[m * L + x[m]], 1u);
+        }
+    };
+    const int64_t hi4 = lo + ((hi - lo) & ~(int64_t)3);
+    if (((uintptr_t)assign & 15) == 0) {
+        // main part: one 16-byte load = 4 assignments per lane, UNR of them in flight.  For M = 4 the
+        // 4 codes (16 bytes) are loaded alongside, unconditionally, so that no load depends on a match.
+        constexpr int UNR = 8;
+        const int4* a4 = reinterpret_cast<const int4*>(assign);
+        const uint4* c4 = reinterpret_cast<const uint4*>(codes);
+        const bool codes16 = (M == 4) && ((uintptr_t)codes & 15) == 0;
+        const int64_t q_lo = lo / 4, q_hi = hi4 / 4;
+        auto add4 = [&](int kk, uint32_t p) {
+            uint32_t* h = lh + (size_t)kk * 4 * L;
+            atomicAdd(&h[0 * L + (p & 255u)], 1u);
+            atomicAdd(&h[1 * L + ((p >> 8) & 255u)], 1u);
+            atomicAdd(&h[2 * L + ((p >> 16) & 255u)], 1u);
+            atomicAdd(&h[3 * L + (p >> 24)], 1u);
+        };
+        for (int64_t qb = q_lo + tid; qb < q_hi; qb += (int64_t)1024 * UNR) {
+            int4 kk[UNR];
+            uint4 cc[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                int64_t qi = qb + (int64_t)u * 1024;
+                kk[u] = (qi < q_hi) ? a4[qi] : make_int4(-1, -1, -1, -1);
+                if (codes16) cc[u] = (qi < q_hi) ? c4[qi] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                int64_t n = (qb + (int64_t)u * 1024) * 4;
+                int d0 = kk[u].x - k0, d1 = kk[u].y - k0, d2 = kk[u].z - k0, d3 = kk[u].w - k0;
+                bool m0 = kk[u].x >= 0 && (unsigned)d0 < (unsigned)kt, m1 = kk[u].y >= 0 && (unsigned)d1 < (unsigned)kt;
+                bool m2 = kk[u].z >= 0 && (unsigned)d2 < (unsigned)kt, m3 = kk[u].w >= 0 && (unsigned)d3 < (unsigned)kt;
+                if (codes16) {
+                    if (m0) add4(d0, cc[u].x);
+                    if (m1) add4(d1, cc[u].y);
+                    if (m2) add4(d2, cc[u].z);
+                    if (m3) add4(d3, cc[u].w);
+                } else {
+                    if (m0) add_code(d0, n);
+                    if (m1) add_code(d1, n + 1);
+                    if (m2) add_code(d2, n + 2);
+                    if (m3) add_code(d3, n + 3);
+                }
+            }
+        }
+    } else {
+        for (int64_t n = lo + tid; n < hi4; n += 1024) {
+            int k = assign[n];
+            if (k >= 0 && (unsigned)(k - k0) < (unsigned)kt) add_code(k - k0, n);
+        }
+    }
+    for (int64_t n = hi4 + tid; n < hi; n += 1024) {
+        int k = assign[n];
+        if (k >= 0 && (unsigned)(k - k0) < (unsigned)kt) add_code(k - k0, n);
+    }
+    __syncthreads();
+    uint32_t* out = hist + (size_t)s * part_stride + (size_t)k0 * M * L;
+    for (int i = tid; i < words; i += 1024) out[i] = lh[i];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Eq. 8: sparse vote.  One wavefront per (center k, subspace m); lane i owns candidates
 // l = 4i..4i+3.  Non-zero bins are visited in ascending j (ballot over 64-bin chunks), each one
 // costing a coalesced 1 KB read of row A^m[j][.] and one fmaf per candidate.  The 256-way argmin
 // is a per-lane ascending strict "<" followed by a (value, index) merge across the wave.
+// The cluster size is the sum of the bins (the same for every subspace); an empty cluster keeps
+// its code, and the wave of subspace 0 stores the size to counts[k].
+// If the histogram arrives as S > 1 partial arrays (parts + s*part_stride), they are added here
+// (integer, exact) and the total is stored to hist.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void vote_kernel(const uint32_t* __restrict__ hist,
-                                                   const uint32_t* __restrict__ counts, int K, int M,
-                                                   const float* __restrict__ tables, uint8_t* __restrict__ centers)
+__global__ __launch_bounds__(256) void vote_kernel(uint32_t* __restrict__ hist, const uint32_t* __restrict__ parts,
+                                                   int S, size_t part_stride, uint32_t* __restrict__ counts,
+                                                   int K, int M, const float* __restrict__ tables,
+                                                   uint8_t* __restrict__ centers)
 {
     const int lane = threadIdx.x & 63;
     const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (pair >= (int64_t)K * M) return;
     const int k = (int)(pair / M), m = (int)(pair % M);
-    if (counts[k] == 0) return;                                  // empty cluster keeps its code
-    const uint32_t* h = hist + (size_t)pair * L;
     const float* A = tables + (size_t)m * L * L;
+    uint32_t hv[4];
+    uint32_t cnt = 0;
+    if (S > 1) {
+#pragma unroll
+        for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = 0u;
+        for (int sl = 0; sl < S; ++sl) {
+            const uint32_t* h = parts + (size_t)sl * part_stride + (size_t)pair * L;
+#pragma unroll
+            for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] += h[chunk * 64 + lane];
+        }
+#pragma unroll
+        for (int chunk = 0; chunk < 4; ++chunk) hist[(size_t)pair * L + chunk * 64 + lane] = hv[chunk];
+    } else {
+        const uint32_t* h = hist + (size_t)pair * L;
+#pragma unroll
+        for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = h[chunk * 64 + lane];
+    }
+#pragma unroll
+    for (int chunk = 0; chunk < 4; ++chunk) cnt += hv[chunk];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+    if (m == 0 && lane == 0) counts[k] = cnt;
+    if (cnt == 0) return;                                        // empty cluster keeps its code
     float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
+#pragma unroll
     for (int chunk = 0; chunk < 4; ++chunk) {
-        uint32_t hv = h[chunk * 64 + lane];
-        uint64_t mask = __ballot(hv != 0u);
+        uint64_t mask = __ballot(hv[chunk] != 0u);
         while (mask) {
             int jl = __ffsll((unsigned long long)mask) - 1;
             mask &= mask - 1;
-            float hf = (float)__shfl(hv, jl);
+            float hf = (float)__shfl(hv[chunk], jl);
             float4 row = *reinterpret_cast<const float4*>(A + (size_t)(chunk * 64 + jl) * L + lane * 4);
             v0 = fmaf(hf, row.x, v0);
             v1 = fmaf(hf, row.y, v1);

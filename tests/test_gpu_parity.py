@@ -88,7 +88,7 @@ def test_assign_generic_matches_oracle(env, M):
     _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=1)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29])
 def test_assign_every_compiled_shape(env, variant):
     w = workload(1, N=9001, K=131, T=40)
     W = env["W"]
@@ -134,9 +134,19 @@ def test_assign_degenerate_inputs(env):
 
 
 # ------------------------------------------------------------------------------------ update
-@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000)])
-def test_update_matches_oracle(env, M, K, N):
+@pytest.mark.parametrize("hist_kernel", [0, 1, 2])
+@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000), (4, 70, 300_000)])
+def test_update_matches_oracle(env, M, K, N, hist_kernel):
     rng = np.random.default_rng(M * K)
+    pq, oracle = env["pq"], env["oracle"]
+    pq.set_option("hist_kernel", hist_kernel)
+    try:
+        _update_case(env, rng, M, K, N)
+    finally:
+        pq.set_option("hist_kernel", 0)
+
+
+def _update_case(env, rng, M, K, N):
     pq, oracle = env["pq"], env["oracle"]
     for integer in (False, True):
         tables = rand_tables(rng, M, integer=integer)

@@ -415,3 +415,19 @@ def test_fit_zero_iterations_and_empty_input(small_problem):
     new, hist, counts = oracle.update(codes[:0], a, tables, centers)
     np.testing.assert_array_equal(new, centers)
     assert hist.sum() == 0 and counts.sum() == 0
+
+
+def test_oracle_reproduces_the_stored_config1_run():
+    """Regression pin: the stored run of configuration 1 (written by tests/golden/make_golden.py,
+    which calls only the oracle) is reproduced bit for bit.  The objectives in it decrease."""
+    import os
+    import sys
+
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    sys.path.insert(0, here)
+    import make_golden
+
+    stored = [l.rstrip("\n") for l in open(os.path.join(here, "config1_fit.txt")) if not l.startswith("#")]
+    assert make_golden.compute() == stored
+    objs = [float(l.split()[3]) for l in stored if l.startswith("iter")]
+    assert all(b <= a for a, b in zip(objs, objs[1:])) and len(objs) == 5
