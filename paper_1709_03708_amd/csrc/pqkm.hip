@@ -33,7 +33,8 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
-    size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, total;
+    size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
+        gid_bytes, total;
 };
 
 // Shape of the LDS-privatised histogram pass: KT clusters per workgroup, `groups` cluster groups, S code slices.
@@ -47,8 +48,8 @@ HistPlan hist_plan(int64_t N, int M, int K)
     p.groups = ((int64_t)K + p.KT - 1) / p.KT;
     p.S = 1;
     while (p.groups * p.S < 256 && p.S < 8 && N / (2 * p.S) >= 8192) p.S *= 2;
-    // every cluster group streams the whole assignment array: worth it while that stays small
-    p.cheap = (double)p.groups * (double)N * 4.0 <= 4.0e9;
+    // every cluster group streams one byte per code: worth it while the groups fit a byte and that stays small
+    p.cheap = p.groups <= 255 && (double)p.groups * (double)N <= 2.0e9;
     return p;
 }
 
@@ -73,6 +74,9 @@ Carve carve(int64_t N, int M, int K)
     HistPlan hp = hist_plan(N, M, K);
     c.parts_bytes = (hp.KT >= 1 && hp.S > 1) ? (size_t)hp.S * align256(c.hist_bytes) : 0;
     off += c.parts_bytes;
+    c.gid_off = off;
+    c.gid_bytes = (hp.KT >= 1 && hp.groups <= 255) ? (size_t)N : 0;
+    off += align256(c.gid_bytes);
     c.total = off;
     return c;
 }
@@ -278,7 +282,7 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
         std::lock_guard<std::mutex> lk(g_mu);
         force = g_opt.hist_kernel;
     }
-    const bool owner = hp.KT >= 1 && force != 1 && (force == 2 || hp.cheap);
+    const bool owner = hp.KT >= 1 && hp.groups <= 255 && force != 1 && (force == 2 || hp.cheap);
     int S = 1;
     size_t part_stride = 0;
     uint32_t* parts = hist;
@@ -288,8 +292,12 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
             parts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.parts_off);
             part_stride = align256(c.hist_bytes) / sizeof(uint32_t);
         }
+        uint8_t* gid = reinterpret_cast<uint8_t*>(static_cast<char*>(ws) + c.gid_off);
+        if (N > 0)
+            hipLaunchKernelGGL(cluster_group_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, assign, N, K,
+                               hp.KT, gid);
         hipLaunchKernelGGL(histogram_owner_kernel, dim3((unsigned)(hp.groups * S)), dim3(1024), 0, st, codes, N, M,
-                           assign, K, hp.KT, S, parts, part_stride);
+                           assign, gid, K, hp.KT, S, parts, part_stride);
     } else {
         zero_hist();
         const int64_t per = (int64_t)1 << 30;
@@ -299,9 +307,13 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
                                codes + n0 * M, cnt, M, assign + n0, K, hist);
         }
     }
-    int64_t pairs = (int64_t)K * M;
-    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, st, hist, parts, S, part_stride,
-                       counts, K, M, tables, centers);
+    // vote: one workgroup per (subspace, CW clusters); about a thousand workgroups, at least one cluster per wave
+    int64_t cw = ((int64_t)K * M + 1023) / 1024;
+    cw = ((cw + 15) / 16) * 16;
+    if (cw > VOTE_MAX_CW) cw = VOTE_MAX_CW;
+    const int64_t blocks_per_m = ((int64_t)K + cw - 1) / cw;
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)(blocks_per_m * M)), dim3(1024), 0, st, hist, parts, S, part_stride,
+                       counts, K, M, (int)cw, tables, centers);
     return launched();
 }
 

@@ -564,39 +564,50 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
         }
     }
 
-    constexpr int G = THREADS > 512 ? 1 : 4;
+    // Epilogue: recover the center inside the winning tile, then merge the 4 lanes of the slot.
+    // Only lanes whose minimum equals the slot's minimum can hold the winner, so only they re-read
+    // their 8 sums from the tile image (scattered 16-byte reads: the fewer the better).
+    constexpr int G = THREADS > 512 ? 2 : 4;
     static_assert(R % G == 0, "the epilogue handles codes in groups");
 #pragma unroll 1
     for (int r0 = 0; r0 < R; r0 += G) {
         v4f w[G][8];
+        float bq[G];
+        int tq[G];
+        bool need[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             uint32_t a = 0, b2 = 0;
-            int tx = 0;
+            bq[g] = INFINITY;
+            tq[g] = -1;
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tx = tix[r]; }
-            const char* gbase = reinterpret_cast<const char*>(img + (size_t)(tx < 0 ? 0 : tx) * TILE_F4);
-            const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + PLANE;
-            const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + PLANE;
-            // w[g][0..3]: the lower half-row (centers 4q..4q+3), w[g][4..7]: the upper one (16+4q..)
-            const uint32_t lowsel = par ? 64u : 0u;     // this lane's stored offsets point at half `par`
-            w[g][0] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel));
-            w[g][1] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel));
-            w[g][2] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel));
-            w[g][3] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel));
-            w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel ^ 64u));
-            w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel ^ 64u));
-            w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel ^ 64u));
-            w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel ^ 64u));
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
+            float smin = bq[g];
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+            need[g] = tq[g] >= 0 && bq[g] == smin;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
+            if (need[g]) {
+                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
+                const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + PLANE;
+                const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + PLANE;
+                // w[g][0..3]: the lower half-row (centers 4q..4q+3), w[g][4..7]: the upper one (16+4q..)
+                const uint32_t lowsel = par ? 64u : 0u;     // this lane's stored offsets point at half `par`
+                w[g][0] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel));
+                w[g][1] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel));
+                w[g][2] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel));
+                w[g][3] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel));
+                w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel ^ 64u));
+                w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel ^ 64u));
+                w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel ^ 64u));
+                w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel ^ 64u));
+            }
         }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             float b = INFINITY;
-            int tx = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { b = best[r]; tx = tix[r]; }
             int bi = IDX_NONE;
             v4f lo = w[g][0] + w[g][1];
             lo = lo + w[g][2];
@@ -604,9 +615,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
             v4f hi = w[g][4] + w[g][5];
             hi = hi + w[g][6];
             hi = hi + w[g][7];
-            if (tx >= 0) {
-                const int kb = tx * TK + q * 4;
-                const float bb = b;
+            if (need[g]) {
+                const int kb = tq[g] * TK + q * 4;
+                const float bb = bq[g];
+                b = bb;
                 if (hi.w == bb) { bi = kb + 19; b = hi.w; }
                 if (hi.z == bb) { bi = kb + 18; b = hi.z; }
                 if (hi.y == bb) { bi = kb + 17; b = hi.y; }
@@ -672,181 +684,259 @@ __global__ __launch_bounds__(256) void histogram_atomic_kernel(const uint8_t* __
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 7, owner path: LDS-privatised histograms.  Workgroup (g, s) owns the KT consecutive
-// clusters k0 = g*KT .. and the s-th of S equal slices of the codes; it streams its slice of
-// `assign` (coalesced, several loads in flight per lane), and for the few codes that fall in its
-// cluster range it increments a private copy of their M histograms in LDS (KT*M*1 KB <= 128 KB).
-// The private copy is stored whole (zeros included, so nothing needs clearing): with S = 1 it IS
-// the result; with S > 1 slice s goes to its own partial array out + s*part_stride, and the
-// vote kernel adds the S partials when it loads a histogram.  No global atomics at all -- they
-// resolve outside the XCD-private L2 on this chip and are slow on hot bins.
+// Eq. 7, owner path: LDS-privatised histograms, no global atomics.
+//
+// Clusters are grouped KT at a time (KT*M*1 KB of histograms = 128 KB of LDS).  A first kernel
+// writes one byte per code, the group of its cluster (255 = none).  Workgroup (g, s) then owns
+// group g and the s-th of S slices of the codes: it streams its slice of the group bytes with
+// 16-byte loads (16 codes per lane and load; the byte array is small enough to stay in the
+// XCD's L2 while all groups stream it), pushes the indices of the matching codes to an LDS
+// queue, and after every batch the whole workgroup drains the queue -- one code per lane: load
+// its assignment and subcodes, increment the private histograms with LDS atomics.  The private
+// copy is stored whole (zeros included, so nothing needs clearing): with S = 1 it IS the result;
+// with S > 1 slice s goes to its own partial array out + s*part_stride and the vote kernel adds
+// the partials when it loads a histogram.
 // ---------------------------------------------------------------------------------------------
-constexpr int HIST_LDS_WORDS = 32768;   // 128 KB
+constexpr int HIST_LDS_WORDS = 32768;   // 128 KB of private histograms
+constexpr int HIST_QCAP = 4096;         // queue entries (16 KB)
+
+// One code into the private histograms of its cluster (LDS atomics).  Kept out of line: it is called
+// from many places of the scan loop, most of them cold.
+__device__ __noinline__ void hist_add_code(uint32_t* lh, const uint8_t* __restrict__ codes,
+                                           const int32_t* __restrict__ assign, int64_t n, int M, int k0, int kt,
+                                           bool wide)
+{
+    int kk = assign[n] - k0;
+    if ((unsigned)kk >= (unsigned)kt) return;
+    uint32_t* h = lh + (size_t)kk * M * L;
+    const uint8_t* x = codes + n * M;
+    if (wide) {
+        const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
+        for (int w = 0; w < M / 4; ++w) {
+            uint32_t p = xw[w];
+            atomicAdd(&h[(4 * w + 0) * L + (p & 255u)], 1u);
+            atomicAdd(&h[(4 * w + 1) * L + ((p >> 8) & 255u)], 1u);
+            atomicAdd(&h[(4 * w + 2) * L + ((p >> 16) & 255u)], 1u);
+            atomicAdd(&h[(4 * w + 3) * L + (p >> 24)], 1u);
+        }
+    } else {
+        for (int m = 0; m < M; ++m) atomicAdd(&h[m * L + x[m]], 1u);
+    }
+}
+
+__global__ __launch_bounds__(256) void cluster_group_kernel(const int32_t* __restrict__ assign, int64_t N, int K,
+                                                            int KT, uint8_t* __restrict__ gid)
+{
+    int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    int k = assign[n];
+    gid[n] = ((unsigned)k < (unsigned)K) ? (uint8_t)(k / KT) : (uint8_t)255;
+}
 
 __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
-                                                               const int32_t* __restrict__ assign, int K, int KT,
+                                                               const int32_t* __restrict__ assign,
+                                                               const uint8_t* __restrict__ gid, int K, int KT,
                                                                int S, uint32_t* __restrict__ hist,
                                                                size_t part_stride)
 {
     __shared__ uint32_t lh[HIST_LDS_WORDS];
+    __shared__ uint32_t queue[HIST_QCAP];
+    __shared__ uint32_t qn;
     const int tid = threadIdx.x;
     const int g = blockIdx.x / S, s = blockIdx.x % S;
     const int k0 = g * KT;
     const int kt = (K - k0 < KT) ? K - k0 : KT;
     const int words = kt * M * L;
     for (int i = tid; i < words; i += 1024) lh[i] = 0u;
+    if (tid == 0) qn = 0u;
     __syncthreads();
 
-    // slice [lo, hi) of the codes, cut at multiples of 4 so that 16-byte loads stay aligned
-    const int64_t lo = (N * s / S) & ~(int64_t)3;
-    const int64_t hi = (s + 1 == S) ? N : ((N * (s + 1) / S) & ~(int64_t)3);
+    // slice [lo, hi) of the codes, cut at multiples of 16 so that 16-byte loads of gid stay aligned
+    const int64_t lo = (N * s / S) & ~(int64_t)15;
+    const int64_t hi = (s + 1 == S) ? N : ((N * (s + 1) / S) & ~(int64_t)15);
     const bool wide = (M & 3) == 0 && ((uintptr_t)codes & 3) == 0;
-    auto add_code = [&](int kk, int64_t n) {
-        uint32_t* h = lh + (size_t)kk * M * L;
-        const uint8_t* x = codes + n * M;
-        if (wide) {
-            const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
-            for (int w = 0; w < M / 4; ++w) {
-                uint32_t p = xw[w];
-                atomicAdd(&h[(4 * w + 0) * L + (p & 255u)], 1u);
-                atomicAdd(&h[(4 * w + 1) * L + ((p >> 8) & 255u)], 1u);
-                atomicAdd(&h[(4 * w + 2) * L + ((p >> 16) & 255u)], 1u);
-                atomicAdd(&h[(4 * w + 3) * L + (p >> 24)], 1u);
-            }
-        } else {
-            for (int m = 0; m < M; ++m) atomicAdd(&h[m * L + x[m]], 1u);
-        }
+    auto add_code = [&](int64_t n) { hist_add_code(lh, codes, assign, n, M, k0, kt, wide); };
+    auto push = [&](int64_t n) {
+        uint32_t slot = atomicAdd(&qn, 1u);
+        if (slot < (uint32_t)HIST_QCAP) queue[slot] = (uint32_t)(n - lo);
+        else add_code(n);                                  // queue full: count it right away
     };
-    const int64_t hi4 = lo + ((hi - lo) & ~(int64_t)3);
-    if (((uintptr_t)assign & 15) == 0) {
-        // main part: one 16-byte load = 4 assignments per lane, UNR of them in flight.  For M = 4 the
-        // 4 codes (16 bytes) are loaded alongside, unconditionally, so that no load depends on a match.
-        constexpr int UNR = 8;
-        const int4* a4 = reinterpret_cast<const int4*>(assign);
-        const uint4* c4 = reinterpret_cast<const uint4*>(codes);
-        const bool codes16 = (M == 4) && ((uintptr_t)codes & 15) == 0;
-        const int64_t q_lo = lo / 4, q_hi = hi4 / 4;
-        auto add4 = [&](int kk, uint32_t p) {
-            uint32_t* h = lh + (size_t)kk * 4 * L;
-            atomicAdd(&h[0 * L + (p & 255u)], 1u);
-            atomicAdd(&h[1 * L + ((p >> 8) & 255u)], 1u);
-            atomicAdd(&h[2 * L + ((p >> 16) & 255u)], 1u);
-            atomicAdd(&h[3 * L + (p >> 24)], 1u);
-        };
-        for (int64_t qb = q_lo + tid; qb < q_hi; qb += (int64_t)1024 * UNR) {
-            int4 kk[UNR];
-            uint4 cc[UNR];
+    auto drain = [&]() {
+        __syncthreads();
+        const uint32_t cnt = qn < (uint32_t)HIST_QCAP ? qn : (uint32_t)HIST_QCAP;
+        for (uint32_t i = tid; i < cnt; i += 1024) add_code(lo + queue[i]);
+        __syncthreads();
+        if (tid == 0) qn = 0u;
+        __syncthreads();
+    };
+
+    const int64_t hi16 = lo + ((hi - lo) & ~(int64_t)15);
+    const uint32_t gg = (uint32_t)g * 0x01010101u;
+    if (((uintptr_t)gid & 15) == 0 && hi - lo < ((int64_t)1 << 32)) {
+        constexpr int UNR = 4;
+        const uint4* g4 = reinterpret_cast<const uint4*>(gid);
+        const int64_t v_lo = lo / 16, v_hi = hi16 / 16;
+        for (int64_t vb = v_lo; vb < v_hi; vb += (int64_t)1024 * UNR) {      // uniform trip count: barriers inside
+            uint4 w[UNR];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
-                int64_t qi = qb + (int64_t)u * 1024;
-                kk[u] = (qi < q_hi) ? a4[qi] : make_int4(-1, -1, -1, -1);
-                if (codes16) cc[u] = (qi < q_hi) ? c4[qi] : make_uint4(0, 0, 0, 0);
+                int64_t vi = vb + (int64_t)u * 1024 + tid;
+                w[u] = (vi < v_hi) ? g4[vi] : make_uint4(~0u, ~0u, ~0u, ~0u);
             }
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
-                int64_t n = (qb + (int64_t)u * 1024) * 4;
-                int d0 = kk[u].x - k0, d1 = kk[u].y - k0, d2 = kk[u].z - k0, d3 = kk[u].w - k0;
-                bool m0 = kk[u].x >= 0 && (unsigned)d0 < (unsigned)kt, m1 = kk[u].y >= 0 && (unsigned)d1 < (unsigned)kt;
-                bool m2 = kk[u].z >= 0 && (unsigned)d2 < (unsigned)kt, m3 = kk[u].w >= 0 && (unsigned)d3 < (unsigned)kt;
-                if (codes16) {
-                    if (m0) add4(d0, cc[u].x);
-                    if (m1) add4(d1, cc[u].y);
-                    if (m2) add4(d2, cc[u].z);
-                    if (m3) add4(d3, cc[u].w);
-                } else {
-                    if (m0) add_code(d0, n);
-                    if (m1) add_code(d1, n + 1);
-                    if (m2) add_code(d2, n + 2);
-                    if (m3) add_code(d3, n + 3);
+                const int64_t n0 = (vb + (int64_t)u * 1024 + tid) * 16;
+                const uint32_t ww[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t x = ww[j] ^ gg;                               // a zero byte marks a match
+                    if (((x - 0x01010101u) & ~x & 0x80808080u) != 0u) {
+                        if ((x & 0x000000ffu) == 0u) push(n0 + 4 * j);
+                        if ((x & 0x0000ff00u) == 0u) push(n0 + 4 * j + 1);
+                        if ((x & 0x00ff0000u) == 0u) push(n0 + 4 * j + 2);
+                        if ((x & 0xff000000u) == 0u) push(n0 + 4 * j + 3);
+                    }
                 }
             }
+            drain();
         }
     } else {
-        for (int64_t n = lo + tid; n < hi4; n += 1024) {
-            int k = assign[n];
-            if (k >= 0 && (unsigned)(k - k0) < (unsigned)kt) add_code(k - k0, n);
+        for (int64_t nb = lo; nb < hi16; nb += 1024 * 4) {
+            for (int u = 0; u < 4; ++u) {
+                int64_t n = nb + (int64_t)u * 1024 + tid;
+                if (n < hi16 && gid[n] == (uint8_t)g) push(n);
+            }
+            drain();
         }
     }
-    for (int64_t n = hi4 + tid; n < hi; n += 1024) {
-        int k = assign[n];
-        if (k >= 0 && (unsigned)(k - k0) < (unsigned)kt) add_code(k - k0, n);
-    }
+    for (int64_t n = hi16 + tid; n < hi; n += 1024)
+        if (gid[n] == (uint8_t)g) add_code(n);
     __syncthreads();
     uint32_t* out = hist + (size_t)s * part_stride + (size_t)k0 * M * L;
     for (int i = tid; i < words; i += 1024) out[i] = lh[i];
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 8: sparse vote.  One wavefront per (center k, subspace m); lane i owns candidates
-// l = 4i..4i+3.  Non-zero bins are visited in ascending j (ballot over 64-bin chunks), each one
-// costing a coalesced 1 KB read of row A^m[j][.] and one fmaf per candidate.  The 256-way argmin
-// is a per-lane ascending strict "<" followed by a (value, index) merge across the wave.
-// The cluster size is the sum of the bins (the same for every subspace); an empty cluster keeps
-// its code, and the wave of subspace 0 stores the size to counts[k].
-// If the histogram arrives as S > 1 partial arrays (parts + s*part_stride), they are added here
-// (integer, exact) and the total is stored to hist.
+// Eq. 8: sparse vote with the table in LDS.
+//
+// A workgroup (1024 threads = 16 waves) serves one subspace m and CW consecutive clusters.  It
+// holds half of A^m in LDS -- A^m[j][l] for all 256 member bins j and 128 of the 256 candidates
+// l (128 KB) -- and runs twice, once per candidate half.  A wave takes one cluster at a time:
+// lane i owns candidates 2i, 2i+1 of the half; non-zero bins are found with a ballot over 64-bin
+// chunks and visited in ascending j, each costing one conflict-free 512-byte LDS row read and
+// one fmaf per candidate (v accumulates in fp32 from 0, exactly as Eq. 8 is read here).  The
+// 128-way argmin is a per-lane ascending strict "<" and a (value, index) xor-shuffle merge; the
+// first half's winner is parked in LDS and the second half replaces it only if strictly
+// smaller, so the lowest index wins ties.  The cluster size is the sum of the bins (the same for
+// every subspace): an empty cluster keeps its code, and subspace 0 stores the size to counts[k].
+// If the histogram arrives as S > 1 partial arrays they are added while loading (integer,
+// exact) and the total is stored to hist during the first half.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void vote_kernel(uint32_t* __restrict__ hist, const uint32_t* __restrict__ parts,
-                                                   int S, size_t part_stride, uint32_t* __restrict__ counts,
-                                                   int K, int M, const float* __restrict__ tables,
-                                                   uint8_t* __restrict__ centers)
+constexpr int VOTE_MAX_CW = 4000;        // clusters per workgroup (parking space: 32 KB of LDS)
+
+__global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist, const uint32_t* __restrict__ parts,
+                                                    int S, size_t part_stride, uint32_t* __restrict__ counts,
+                                                    int K, int M, int CW, const float* __restrict__ tables,
+                                                    uint8_t* __restrict__ centers)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (pair >= (int64_t)K * M) return;
-    const int k = (int)(pair / M), m = (int)(pair % M);
+    __shared__ float4 At[L * 128 / 4];          // [j][128 candidates]
+    __shared__ float pv[VOTE_MAX_CW];           // first half: best value per cluster
+    __shared__ int pi[VOTE_MAX_CW];             // first half: its candidate
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int blocks_per_m = (K + CW - 1) / CW;
+    const int m = blockIdx.x / blocks_per_m;
+    const int c0 = (blockIdx.x % blocks_per_m) * CW;
+    const int cn = (K - c0 < CW) ? K - c0 : CW;
     const float* A = tables + (size_t)m * L * L;
-    uint32_t hv[4];
-    uint32_t cnt = 0;
-    if (S > 1) {
+
+    for (int half = 0; half < 2; ++half) {
+        __syncthreads();                        // the previous half is no longer being read
 #pragma unroll
-        for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = 0u;
-        for (int sl = 0; sl < S; ++sl) {
-            const uint32_t* h = parts + (size_t)sl * part_stride + (size_t)pair * L;
-#pragma unroll
-            for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] += h[chunk * 64 + lane];
+        for (int i = 0; i < 8; ++i) {
+            int f = i * 1024 + tid;             // float4 index in the half table: row j = f / 32, column quad f % 32
+            At[f] = *reinterpret_cast<const float4*>(A + (size_t)(f >> 5) * L + half * 128 + (f & 31) * 4);
         }
+        __syncthreads();
+        for (int c = wave; c < cn; c += 16) {
+            const int k = c0 + c;
+            const size_t pair = (size_t)k * M + m;
+            uint32_t hv[4];
+            if (S > 1) {
 #pragma unroll
-        for (int chunk = 0; chunk < 4; ++chunk) hist[(size_t)pair * L + chunk * 64 + lane] = hv[chunk];
-    } else {
-        const uint32_t* h = hist + (size_t)pair * L;
+                for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = 0u;
+                for (int sl = 0; sl < S; ++sl) {
+                    const uint32_t* h = parts + (size_t)sl * part_stride + pair * L;
 #pragma unroll
-        for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = h[chunk * 64 + lane];
-    }
+                    for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] += h[chunk * 64 + lane];
+                }
+                if (half == 0) {
 #pragma unroll
-    for (int chunk = 0; chunk < 4; ++chunk) cnt += hv[chunk];
+                    for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[chunk];
+                }
+            } else {
+                const uint32_t* h = hist + pair * L;
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
-    if (m == 0 && lane == 0) counts[k] = cnt;
-    if (cnt == 0) return;                                        // empty cluster keeps its code
-    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;
+                for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = h[chunk * 64 + lane];
+            }
+            uint32_t cnt = hv[0] + hv[1] + hv[2] + hv[3];
 #pragma unroll
-    for (int chunk = 0; chunk < 4; ++chunk) {
-        uint64_t mask = __ballot(hv[chunk] != 0u);
-        while (mask) {
-            int jl = __ffsll((unsigned long long)mask) - 1;
-            mask &= mask - 1;
-            float hf = (float)__shfl(hv[chunk], jl);
-            float4 row = *reinterpret_cast<const float4*>(A + (size_t)(chunk * 64 + jl) * L + lane * 4);
-            v0 = fmaf(hf, row.x, v0);
-            v1 = fmaf(hf, row.y, v1);
-            v2 = fmaf(hf, row.z, v2);
-            v3 = fmaf(hf, row.w, v3);
+            for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+            if (half == 0 && m == 0 && lane == 0) counts[k] = cnt;
+            if (cnt == 0) continue;                                  // empty cluster keeps its code
+            float v0 = 0.0f, v1 = 0.0f;
+            const float2* At2 = reinterpret_cast<const float2*>(At);
+#pragma unroll
+            for (int chunk = 0; chunk < 4; ++chunk) {
+                uint64_t mask = __ballot(hv[chunk] != 0u);
+                const float2* rows = At2 + chunk * 64 * 64 + lane;
+                // four bins at a time: their LDS rows are fetched together, the fmas stay in ascending j
+                while (__popcll(mask) >= 4) {
+                    int j0 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
+                    int j1 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
+                    int j2 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
+                    int j3 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
+                    float2 r0 = rows[j0 * 64], r1 = rows[j1 * 64], r2 = rows[j2 * 64], r3 = rows[j3 * 64];
+                    float h0 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j0);
+                    float h1 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j1);
+                    float h2 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j2);
+                    float h3 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j3);
+                    v0 = fmaf(h0, r0.x, v0); v1 = fmaf(h0, r0.y, v1);
+                    v0 = fmaf(h1, r1.x, v0); v1 = fmaf(h1, r1.y, v1);
+                    v0 = fmaf(h2, r2.x, v0); v1 = fmaf(h2, r2.y, v1);
+                    v0 = fmaf(h3, r3.x, v0); v1 = fmaf(h3, r3.y, v1);
+                }
+                while (mask) {
+                    int jl = __ffsll((unsigned long long)mask) - 1;
+                    mask &= mask - 1;
+                    float hf = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], jl);
+                    float2 row = rows[jl * 64];
+                    v0 = fmaf(hf, row.x, v0);
+                    v1 = fmaf(hf, row.y, v1);
+                }
+            }
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            if (v0 < b) { b = v0; bi = half * 128 + lane * 2; }
+            if (v1 < b) { b = v1; bi = half * 128 + lane * 2 + 1; }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            if (lane == 0) {
+                if (half == 0) {
+                    pv[c] = b;
+                    pi[c] = bi;
+                } else {
+                    float fb = pv[c];
+                    int fi = pi[c];
+                    if (b < fb) { fb = b; fi = bi; }
+                    centers[pair] = (uint8_t)((fi == IDX_NONE) ? 0 : fi);
+                }
+            }
         }
     }
-    float b = INFINITY;
-    int bi = IDX_NONE;
-    if (v0 < b) { b = v0; bi = lane * 4; }
-    if (v1 < b) { b = v1; bi = lane * 4 + 1; }
-    if (v2 < b) { b = v2; bi = lane * 4 + 2; }
-    if (v3 < b) { b = v3; bi = lane * 4 + 3; }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        float ob = __shfl_xor(b, d);
-        int oi = __shfl_xor(bi, d);
-        if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-    }
-    if (lane == 0) centers[pair] = (uint8_t)((bi == IDX_NONE) ? 0 : bi);
 }
 
 }  // namespace pqkm
