@@ -140,6 +140,20 @@ void launch_scan4x2(const uint8_t* codes, int64_t N, const float4* img, int ntil
                        img, ntiles, assign, dist);
 }
 
+template <int R, int THREADS>
+void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                   hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4s_kernel<R, THREADS>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, img,
+                       ntiles, assign, dist);
+}
+
+// the subspace-skewed scans read an x-major tile image
+// (variant 0, the default for M = 4, is the skewed scan with 16 codes per lane-slot and 1024 threads)
+inline bool variant_xmajor(int M, int variant) { return M == 4 && (variant == 0 || (variant >= 30 && variant <= 39)); }
+
 template <int M>
 void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                    float* dist, hipStream_t st);
@@ -177,11 +191,17 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 27: launch_scan4x2<28, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 28: launch_scan4x2<14, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 29: launch_scan4x2<20, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        default:
-            // few tiles: the per-workgroup prologue/epilogue matters, more waves hide it better
-            if (ntiles <= 64) launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st);
-            else launch_scan4x2<32, 512, true>(codes, N, img, ntiles, assign, dist, st);
-            break;
+        case 30: launch_scan4s<24, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 31: launch_scan4s<24, 768>(codes, N, img, ntiles, assign, dist, st); break;
+        case 32: launch_scan4s<16, 768>(codes, N, img, ntiles, assign, dist, st); break;
+        case 33: launch_scan4s<12, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 34: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 35: launch_scan4s<20, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 36: launch_scan4s<16, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 37: launch_scan4s<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 38: launch_scan4s<20, 768>(codes, N, img, ntiles, assign, dist, st); break;
+        case 39: launch_scan4s<14, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        default: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
 template <>
@@ -210,8 +230,12 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     constexpr int TK = 128 / M;
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
-    hipLaunchKernelGGL((tile_image_kernel<M>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, centers, K,
-                       tables, img, total);
+    if (variant_xmajor(M, opt.scan_variant))
+        hipLaunchKernelGGL((tile_image_kernel<M, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           centers, K, tables, img, total);
+    else
+        hipLaunchKernelGGL((tile_image_kernel<M, false>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           centers, K, tables, img, total);
     if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
     for (int64_t n0 = 0; n0 < N; n0 += opt.launch_codes) {
         int64_t cnt = N - n0 < opt.launch_codes ? N - n0 : opt.launch_codes;

@@ -81,7 +81,9 @@ __global__ __launch_bounds__(256) void assign_generic_kernel(const uint8_t* __re
 // subcodes rather than all on the same ones.  Centers past K are padded with +inf, which a
 // strict "<" never selects.  One thread per element, kin fastest, so stores are contiguous.
 // ---------------------------------------------------------------------------------------------
-template <int M>
+// XMAJOR selects the alternative order img[tile][x][m][kin] used by the subspace-skewed scan, in which
+// the LDS bank half of a row is decided by the parity of m instead of the parity of x.
+template <int M, bool XMAJOR = false>
 __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restrict__ centers, int K,
                                                          const float* __restrict__ tables, float* __restrict__ img,
                                                          int64_t total)
@@ -90,8 +92,14 @@ __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restri
     int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
     int kin = (int)(e % TK);
-    int x = (int)((e / TK) % L);
-    int m = (int)((e / (TK * L)) % M);
+    int x, m;
+    if (XMAJOR) {
+        m = (int)((e / TK) % M);
+        x = (int)((e / (TK * M)) % L);
+    } else {
+        x = (int)((e / TK) % L);
+        m = (int)((e / (TK * L)) % M);
+    }
     int64_t tile = e / ((int64_t)TK * M * L);
     int64_t k = tile * TK + kin;
     float v = INFINITY;
@@ -603,6 +611,212 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
                 w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel ^ 64u));
                 w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel ^ 64u));
                 w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel ^ 64u));
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            v4f lo = w[g][0] + w[g][1];
+            lo = lo + w[g][2];
+            lo = lo + w[g][3];
+            v4f hi = w[g][4] + w[g][5];
+            hi = hi + w[g][6];
+            hi = hi + w[g][7];
+            if (need[g]) {
+                const int kb = tq[g] * TK + q * 4;
+                const float bb = bq[g];
+                b = bb;
+                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
+                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
+                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
+                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
+                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
+                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
+                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
+                if (lo.x == bb) { bi = kb; b = lo.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                assign[n] = (bi == IDX_NONE) ? 0 : bi;
+                if (dist) dist[n] = b;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 4 scan with conflict-free LDS reads ("subspace skew").
+//
+// Same decomposition as assign_scan4x2_kernel (4 lanes per slot, 8 centers per lane, TK = 32),
+// but the tile image is x-major -- row (x, m) at byte x*512 + m*128 -- so that a row's LDS bank
+// half is the parity of m and its quarter the half-row.  A 16-byte-per-lane LDS read is served
+// 16 lanes = 4 slots per clock; the four slots of a group are made to hit four different bank
+// quarters in every read: slots 0,1 of the group read subspace i in step i, slots 2,3 read
+// subspace i-1 (one step behind); slots 0,2 take the lower half-row first, slots 1,3 the upper.
+// The price of the skew is a fifth step per code: in the step a slot has no subspace to read it
+// reads a line of -0.0 placed after the tile, and the sum becomes a chain of five terms
+// (((V0 + V1) + V2) + V3) + V4 in which the -0.0 comes first or last.  Adding -0.0 returns the
+// other operand bit for bit, so the value is exactly ((A0 + A1) + A2) + A3 in every lane.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS>
+__global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = (TILE_F4 + THREADS - 1) / THREADS;     // float4 per thread per tile fill (last one partial)
+    constexpr bool EVEN = TILE_F4 % THREADS == 0;
+    constexpr uint32_t PAD = TILE_BYTES;      // 256 bytes of -0.0: [PAD, PAD+128) in bank half 0, the rest in half 1
+
+    __shared__ float4 tile[TILE_F4 + 16];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const uint32_t hsel = (uint32_t)c & 1u;           // odd slots start with the upper half-row
+    const uint32_t late = ((uint32_t)c >> 1) & 1u;    // slots 2,3 of a group run one subspace behind
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
+
+    // five step offsets per code, /16, in 16-bit fields: pa = f0|f1, pb = f2|f3; the fifth fields of
+    // codes 2i and 2i+1 share pc[i]
+    static_assert(R % 2 == 0, "fifth offsets are stored two to a register");
+    uint32_t pa[R], pb[R], pc[R / 2];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        const uint32_t lo = (hsel << 2) | (uint32_t)q;                       // (hsel*64 + q*16) / 16
+        uint32_t g0 = ((pk & 255u) << 5) | (0u << 3) | lo;                   // (x*512 + m*128)/16 = x*32 + m*8
+        uint32_t g1 = (((pk >> 8) & 255u) << 5) | (1u << 3) | lo;
+        uint32_t g2 = (((pk >> 16) & 255u) << 5) | (2u << 3) | lo;
+        uint32_t g3 = ((pk >> 24) << 5) | (3u << 3) | lo;
+        uint32_t dz = (PAD >> 4) + ((late ^ 1u) ? 0u : 8u) + lo;             // early slots pad in half 0, late ones in half 1
+        uint32_t f0 = late ? dz : g0, f1 = late ? g0 : g1, f2 = late ? g1 : g2, f3 = late ? g2 : g3,
+                 f4 = late ? g3 : dz;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        if (r & 1) pc[r / 2] |= f4 << 16; else pc[r / 2] = f4;
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    struct Pair { float4 a, b; };
+    auto issue = [&](int r, int i) -> Pair {
+        uint32_t ad = (i == 0) ? sdwa_shl_word0(four, pa[r])
+                    : (i == 1) ? sdwa_shl_word1(four, pa[r])
+                    : (i == 2) ? sdwa_shl_word0(four, pb[r])
+                    : (i == 3) ? sdwa_shl_word1(four, pb[r])
+                    : (r & 1)  ? sdwa_shl_word1(four, pc[r / 2])
+                               : sdwa_shl_word0(four, pc[r / 2]);
+        Pair p;
+        p.a = lds_read16(tb, ad);
+        p.b = lds_read16(tb, ad ^ 64u);
+        return p;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i)
+            if (EVEN || i * THREADS + tid < TILE_F4) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        {
+            const int tn = t + 1 < ntiles ? t + 1 : t;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
+        }
+        Pair cur = issue(0, 0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float4 sa, sb;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                Pair nxt = cur;
+                if (i < 4) nxt = issue(r, i + 1);
+                else if (r + 1 < R) nxt = issue(r + 1, 0);
+                if (i == 0) {
+                    sa = cur.a;
+                    sb = cur.b;
+                } else {
+                    sa.x = sa.x + cur.a.x; sa.y = sa.y + cur.a.y; sa.z = sa.z + cur.a.z; sa.w = sa.w + cur.a.w;
+                    sb.x = sb.x + cur.b.x; sb.y = sb.y + cur.b.y; sb.z = sb.z + cur.b.z; sb.w = sb.w + cur.b.w;
+                }
+                cur = nxt;
+            }
+            float m8 = __builtin_fminf(__builtin_fminf(sa.x, sa.y), sa.z);          // v_min3 chains
+            m8 = __builtin_fminf(__builtin_fminf(m8, sa.w), sb.x);
+            m8 = __builtin_fminf(__builtin_fminf(m8, sb.y), sb.z);
+            m8 = __builtin_fminf(m8, sb.w);
+            tix[r] = (m8 < best[r]) ? t : tix[r];
+            best[r] = __builtin_fminf(best[r], m8);
+        }
+    }
+
+    // Epilogue: as in assign_scan4x2_kernel; the four real subspace offsets are fields 0..3 (early
+    // slots) or 1..4 (late slots), and an offset is the byte position inside the tile image.
+    constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
+    static_assert(R % G == 0, "the epilogue handles codes in groups");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][8];
+        float bq[G];
+        int tq[G];
+        bool need[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint32_t a = 0, b2 = 0, c2 = 0;
+            bq[g] = INFINITY;
+            tq[g] = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; c2 = (r & 1) ? pc[r / 2] >> 16 : pc[r / 2]; tq[g] = tix[r]; bq[g] = best[r]; }
+            float smin = bq[g];
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+            need[g] = tq[g] >= 0 && bq[g] == smin;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
+            if (need[g]) {
+                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
+                const uint32_t e0 = a & 0xffffu, e1 = a >> 16, e2 = b2 & 0xffffu, e3 = b2 >> 16, e4 = c2 & 0xffffu;
+                const uint32_t o0 = ((late ? e1 : e0) << 4) & ~64u, o1 = ((late ? e2 : e1) << 4) & ~64u;
+                const uint32_t o2 = ((late ? e3 : e2) << 4) & ~64u, o3 = ((late ? e4 : e3) << 4) & ~64u;
+                w[g][0] = *reinterpret_cast<const v4f*>(gbase + o0);
+                w[g][1] = *reinterpret_cast<const v4f*>(gbase + o1);
+                w[g][2] = *reinterpret_cast<const v4f*>(gbase + o2);
+                w[g][3] = *reinterpret_cast<const v4f*>(gbase + o3);
+                w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 | 64u));
+                w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 | 64u));
+                w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 | 64u));
+                w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 | 64u));
             }
         }
 #pragma unroll

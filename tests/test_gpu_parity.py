@@ -88,7 +88,7 @@ def test_assign_generic_matches_oracle(env, M):
     _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=1)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31, 32, 33, 34, 35, 36, 37, 38, 39])
 def test_assign_every_compiled_shape(env, variant):
     w = workload(1, N=9001, K=131, T=40)
     W = env["W"]
