@@ -124,6 +124,9 @@ pqkm_status pqkm_fit(const uint8_t *codes, int64_t N, int32_t M, const float *ta
  *                        one specific compiled shape (for tuning sweeps)
  *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
  *                        per code and subspace, 2 = force the LDS-privatised histogram
+ *   "hist_groups"        target number of cluster groups of the LDS-privatised histogram,
+ *                        1..255 (default 64); changes pqkm_workspace_bytes, so set it before
+ *                        sizing the workspace
  *   "launch_codes_log2"  the scan is issued in launches of 2^value codes (default 26)
  *   "profile"            1 = bracket every scan-kernel launch with a pair of HIP
  *                        events on the caller's stream (events are created on

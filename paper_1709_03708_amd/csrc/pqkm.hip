@@ -24,6 +24,7 @@ struct Options {
 };
 Options g_opt;
 std::mutex g_mu;
+int g_hist_groups = 64;    // target number of cluster groups of the LDS-privatised histogram (measured best)
 
 struct EventPair { hipEvent_t a, b; };
 std::vector<EventPair> g_pool;      // all events ever created
@@ -43,11 +44,15 @@ struct HistPlan { int KT; int64_t groups; int S; bool cheap; };
 HistPlan hist_plan(int64_t N, int M, int K)
 {
     HistPlan p{};
-    p.KT = (HIST_LDS_WORDS / L) / M;                       // 128 KB of LDS / (M KB per cluster)
-    if (p.KT < 1) return p;
+    const int kt_max = (HIST_LDS_WORDS / L) / M;           // 128 KB of LDS / (M KB per cluster)
+    if (kt_max < 1) return p;
+    // about g_hist_groups groups (a byte names at most 255), within the LDS budget
+    int kt = (K + g_hist_groups - 1) / g_hist_groups;
+    if (kt > kt_max) kt = kt_max;
+    p.KT = kt;
     p.groups = ((int64_t)K + p.KT - 1) / p.KT;
     p.S = 1;
-    while (p.groups * p.S < 256 && p.S < 8 && N / (2 * p.S) >= 8192) p.S *= 2;
+    while (p.groups * p.S < 192 && p.S < 16 && N / (2 * p.S) >= 8192) p.S *= 2;
     // every cluster group streams one byte per code: worth it while the groups fit a byte and that stays small
     p.cheap = p.groups <= 255 && (double)p.groups * (double)N <= 2.0e9;
     return p;
@@ -320,8 +325,12 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
         if (N > 0)
             hipLaunchKernelGGL(cluster_group_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, assign, N, K,
                                hp.KT, gid);
-        hipLaunchKernelGGL(histogram_owner_kernel, dim3((unsigned)(hp.groups * S)), dim3(1024), 0, st, codes, N, M,
-                           assign, gid, K, hp.KT, S, parts, part_stride);
+        if ((int64_t)hp.KT * M * L <= HIST_LDS_WORDS_SMALL)
+            hipLaunchKernelGGL((histogram_owner_kernel<HIST_LDS_WORDS_SMALL>), dim3((unsigned)(hp.groups * S)),
+                               dim3(1024), 0, st, codes, N, M, assign, gid, K, hp.KT, S, parts, part_stride);
+        else
+            hipLaunchKernelGGL((histogram_owner_kernel<HIST_LDS_WORDS>), dim3((unsigned)(hp.groups * S)), dim3(1024),
+                               0, st, codes, N, M, assign, gid, K, hp.KT, S, parts, part_stride);
     } else {
         zero_hist();
         const int64_t per = (int64_t)1 << 30;
@@ -429,6 +438,9 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
     } else if (strcmp(name, "hist_kernel") == 0) {
         if (value < 0 || value > 2) return PQKM_ERR_SHAPE;
         g_opt.hist_kernel = value;
+    } else if (strcmp(name, "hist_groups") == 0) {
+        if (value < 1 || value > 255) return PQKM_ERR_SHAPE;
+        g_hist_groups = value;
     } else if (strcmp(name, "profile") == 0) {
         if (value < 0 || value > 1) return PQKM_ERR_SHAPE;
         g_opt.profile = value;

@@ -900,7 +900,8 @@ __global__ __launch_bounds__(256) void histogram_atomic_kernel(const uint8_t* __
 // ---------------------------------------------------------------------------------------------
 // Eq. 7, owner path: LDS-privatised histograms, no global atomics.
 //
-// Clusters are grouped KT at a time (KT*M*1 KB of histograms = 128 KB of LDS).  A first kernel
+// Clusters are grouped KT at a time, KT chosen so that there are up to 255 groups (about one
+// per CU) and KT*M*1 KB of histograms fit the LDS budget (16 KB or 128 KB).  A first kernel
 // writes one byte per code, the group of its cluster (255 = none).  Workgroup (g, s) then owns
 // group g and the s-th of S slices of the codes: it streams its slice of the group bytes with
 // 16-byte loads (16 codes per lane and load; the byte array is small enough to stay in the
@@ -911,7 +912,8 @@ __global__ __launch_bounds__(256) void histogram_atomic_kernel(const uint8_t* __
 // with S > 1 slice s goes to its own partial array out + s*part_stride and the vote kernel adds
 // the partials when it loads a histogram.
 // ---------------------------------------------------------------------------------------------
-constexpr int HIST_LDS_WORDS = 32768;   // 128 KB of private histograms
+constexpr int HIST_LDS_WORDS = 32768;   // 128 KB of private histograms (large instantiation)
+constexpr int HIST_LDS_WORDS_SMALL = 4096;   // 16 KB (small instantiation: several workgroups per CU)
 constexpr int HIST_QCAP = 4096;         // queue entries (16 KB)
 
 // One code into the private histograms of its cluster (LDS atomics).  Kept out of line: it is called
@@ -947,13 +949,14 @@ __global__ __launch_bounds__(256) void cluster_group_kernel(const int32_t* __res
     gid[n] = ((unsigned)k < (unsigned)K) ? (uint8_t)(k / KT) : (uint8_t)255;
 }
 
+template <int LDS_WORDS>
 __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
                                                                const int32_t* __restrict__ assign,
                                                                const uint8_t* __restrict__ gid, int K, int KT,
                                                                int S, uint32_t* __restrict__ hist,
                                                                size_t part_stride)
 {
-    __shared__ uint32_t lh[HIST_LDS_WORDS];
+    __shared__ uint32_t lh[LDS_WORDS];
     __shared__ uint32_t queue[HIST_QCAP];
     __shared__ uint32_t qn;
     const int tid = threadIdx.x;
@@ -975,8 +978,8 @@ __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __
         if (slot < (uint32_t)HIST_QCAP) queue[slot] = (uint32_t)(n - lo);
         else add_code(n);                                  // queue full: count it right away
     };
+    // drain(): the whole workgroup empties the queue, one code per lane.  Collective (barriers inside).
     auto drain = [&]() {
-        __syncthreads();
         const uint32_t cnt = qn < (uint32_t)HIST_QCAP ? qn : (uint32_t)HIST_QCAP;
         for (uint32_t i = tid; i < cnt; i += 1024) add_code(lo + queue[i]);
         __syncthreads();
@@ -987,32 +990,45 @@ __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __
     const int64_t hi16 = lo + ((hi - lo) & ~(int64_t)15);
     const uint32_t gg = (uint32_t)g * 0x01010101u;
     if (((uintptr_t)gid & 15) == 0 && hi - lo < ((int64_t)1 << 32)) {
-        constexpr int UNR = 4;
+        constexpr int UNR = 8;
         const uint4* g4 = reinterpret_cast<const uint4*>(gid);
         const int64_t v_lo = lo / 16, v_hi = hi16 / 16;
-        for (int64_t vb = v_lo; vb < v_hi; vb += (int64_t)1024 * UNR) {      // uniform trip count: barriers inside
-            uint4 w[UNR];
+        auto fetch = [&](int64_t vb, uint4 (&w)[UNR]) {
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 int64_t vi = vb + (int64_t)u * 1024 + tid;
                 w[u] = (vi < v_hi) ? g4[vi] : make_uint4(~0u, ~0u, ~0u, ~0u);
             }
+        };
+        // Batches are visited in a rotated order that differs from group to group, so that the
+        // workgroups, which all stream the same bytes, do not all ask the same L2 channel at once.
+        const int64_t nbatch = (v_hi - v_lo + (int64_t)1024 * UNR - 1) / ((int64_t)1024 * UNR);
+        const int64_t rot = nbatch > 0 ? ((int64_t)g * 7 + s) % nbatch : 0;
+        auto batch_base = [&](int64_t b) { return v_lo + ((b + rot) % nbatch) * (int64_t)1024 * UNR; };
+        uint4 w[UNR], wn[UNR];
+        if (nbatch > 0) fetch(batch_base(0), wn);
+        for (int64_t b = 0; b < nbatch; ++b) {                               // uniform trip count: barriers inside
+            const int64_t vb = batch_base(b);
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) w[u] = wn[u];
+            if (b + 1 < nbatch) fetch(batch_base(b + 1), wn);                // next batch in flight
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int64_t n0 = (vb + (int64_t)u * 1024 + tid) * 16;
-                const uint32_t ww[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint32_t x = ww[j] ^ gg;                               // a zero byte marks a match
-                    if (((x - 0x01010101u) & ~x & 0x80808080u) != 0u) {
-                        if ((x & 0x000000ffu) == 0u) push(n0 + 4 * j);
-                        if ((x & 0x0000ff00u) == 0u) push(n0 + 4 * j + 1);
-                        if ((x & 0x00ff0000u) == 0u) push(n0 + 4 * j + 2);
-                        if ((x & 0xff000000u) == 0u) push(n0 + 4 * j + 3);
-                    }
+                // bit 8*b + j of mm is set iff byte b of word j equals g (exact zero-byte test per word)
+                auto zb = [&](uint32_t word) -> uint32_t {
+                    uint32_t x = word ^ gg;
+                    return ~(((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x | 0x7f7f7f7fu);     // 0x80 in every zero byte
+                };
+                uint32_t mm = (zb(w[u].x) >> 7) | (zb(w[u].y) >> 6) | (zb(w[u].z) >> 5) | (zb(w[u].w) >> 4);
+                while (mm) {                                                // 0 or 1 iterations for most lanes
+                    const int bit = __ffs((int)mm) - 1;
+                    mm &= mm - 1;
+                    push(n0 + 4 * (bit & 7) + (bit >> 3));
                 }
             }
-            drain();
+            __syncthreads();
+            if (qn >= (uint32_t)(HIST_QCAP / 2)) drain();                    // same value in every lane after the barrier
         }
     } else {
         for (int64_t nb = lo; nb < hi16; nb += 1024 * 4) {
@@ -1020,9 +1036,12 @@ __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __
                 int64_t n = nb + (int64_t)u * 1024 + tid;
                 if (n < hi16 && gid[n] == (uint8_t)g) push(n);
             }
-            drain();
+            __syncthreads();
+            if (qn >= (uint32_t)(HIST_QCAP / 2)) drain();
         }
     }
+    __syncthreads();
+    drain();
     for (int64_t n = hi16 + tid; n < hi; n += 1024)
         if (gid[n] == (uint8_t)g) add_code(n);
     __syncthreads();
@@ -1036,17 +1055,19 @@ __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __
 // A workgroup (1024 threads = 16 waves) serves one subspace m and CW consecutive clusters.  It
 // holds half of A^m in LDS -- A^m[j][l] for all 256 member bins j and 128 of the 256 candidates
 // l (128 KB) -- and runs twice, once per candidate half.  A wave takes one cluster at a time:
-// lane i owns candidates 2i, 2i+1 of the half; non-zero bins are found with a ballot over 64-bin
-// chunks and visited in ascending j, each costing one conflict-free 512-byte LDS row read and
-// one fmaf per candidate (v accumulates in fp32 from 0, exactly as Eq. 8 is read here).  The
-// 128-way argmin is a per-lane ascending strict "<" and a (value, index) xor-shuffle merge; the
-// first half's winner is parked in LDS and the second half replaces it only if strictly
-// smaller, so the lowest index wins ties.  The cluster size is the sum of the bins (the same for
-// every subspace): an empty cluster keeps its code, and subspace 0 stores the size to counts[k].
-// If the histogram arrives as S > 1 partial arrays they are added while loading (integer,
-// exact) and the total is stored to hist during the first half.
+// it first compacts the non-zero bins of the cluster's histogram, in ascending j, into a small
+// per-wave list in LDS (bin index and count as fp32; ballot + prefix popcount), then walks the
+// list: lane i owns candidates 2i, 2i+1 of the half, and every list entry costs two broadcast
+// LDS reads, one conflict-free 512-byte row read and one fmaf per candidate (v accumulates in
+// fp32 from 0, in ascending j, exactly as Eq. 8 is read here).  The 128-way argmin is a per-lane
+// ascending strict "<" and a (value, index) xor-shuffle merge; the first half's winner is parked
+// in LDS and the second half replaces it only if strictly smaller, so the lowest index wins
+// ties.  The cluster size is the sum of the bins (the same for every subspace): an empty cluster
+// keeps its code, and subspace 0 stores the size to counts[k].  If the histogram arrives as
+// S > 1 partial arrays they are added while loading (integer, exact) and the total is stored to
+// hist during the first half.
 // ---------------------------------------------------------------------------------------------
-constexpr int VOTE_MAX_CW = 4000;        // clusters per workgroup (parking space: 32 KB of LDS)
+constexpr int VOTE_MAX_CW = 1024;        // clusters per workgroup (parking space: 8 KB of LDS)
 
 __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist, const uint32_t* __restrict__ parts,
                                                     int S, size_t part_stride, uint32_t* __restrict__ counts,
@@ -1056,12 +1077,16 @@ __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist,
     __shared__ float4 At[L * 128 / 4];          // [j][128 candidates]
     __shared__ float pv[VOTE_MAX_CW];           // first half: best value per cluster
     __shared__ int pi[VOTE_MAX_CW];             // first half: its candidate
+    __shared__ float lst_h[16][L];              // per wave: counts of the non-zero bins, ascending j
+    __shared__ uint8_t lst_j[16][L];            // per wave: their bin indices
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int blocks_per_m = (K + CW - 1) / CW;
     const int m = blockIdx.x / blocks_per_m;
     const int c0 = (blockIdx.x % blocks_per_m) * CW;
     const int cn = (K - c0 < CW) ? K - c0 : CW;
     const float* A = tables + (size_t)m * L * L;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes below this one
+    const float2* At2 = reinterpret_cast<const float2*>(At);
 
     for (int half = 0; half < 2; ++half) {
         __syncthreads();                        // the previous half is no longer being read
@@ -1075,7 +1100,7 @@ __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist,
             const int k = c0 + c;
             const size_t pair = (size_t)k * M + m;
             uint32_t hv[4];
-            if (S > 1) {
+            if (S > 1 && half == 0) {
 #pragma unroll
                 for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = 0u;
                 for (int sl = 0; sl < S; ++sl) {
@@ -1083,14 +1108,25 @@ __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist,
 #pragma unroll
                     for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] += h[chunk * 64 + lane];
                 }
-                if (half == 0) {
 #pragma unroll
-                    for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[chunk];
-                }
+                for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[chunk];
             } else {
+                // (second half with S > 1: each lane reads back the totals it stored itself)
                 const uint32_t* h = hist + pair * L;
 #pragma unroll
                 for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = h[chunk * 64 + lane];
+            }
+            // compact the non-zero bins (ascending j) into this wave's list; their number is wave-uniform
+            int nnz = 0;
+#pragma unroll
+            for (int chunk = 0; chunk < 4; ++chunk) {
+                const uint64_t mask = __ballot(hv[chunk] != 0u);
+                if (hv[chunk] != 0u) {
+                    const int pos = nnz + __popcll(mask & lt_mask);
+                    lst_h[wave][pos] = (float)hv[chunk];
+                    lst_j[wave][pos] = (uint8_t)(chunk * 64 + lane);
+                }
+                nnz += __popcll(mask);
             }
             uint32_t cnt = hv[0] + hv[1] + hv[2] + hv[3];
 #pragma unroll
@@ -1098,35 +1134,25 @@ __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist,
             if (half == 0 && m == 0 && lane == 0) counts[k] = cnt;
             if (cnt == 0) continue;                                  // empty cluster keeps its code
             float v0 = 0.0f, v1 = 0.0f;
-            const float2* At2 = reinterpret_cast<const float2*>(At);
-#pragma unroll
-            for (int chunk = 0; chunk < 4; ++chunk) {
-                uint64_t mask = __ballot(hv[chunk] != 0u);
-                const float2* rows = At2 + chunk * 64 * 64 + lane;
-                // four bins at a time: their LDS rows are fetched together, the fmas stay in ascending j
-                while (__popcll(mask) >= 4) {
-                    int j0 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
-                    int j1 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
-                    int j2 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
-                    int j3 = __ffsll((unsigned long long)mask) - 1; mask &= mask - 1;
-                    float2 r0 = rows[j0 * 64], r1 = rows[j1 * 64], r2 = rows[j2 * 64], r3 = rows[j3 * 64];
-                    float h0 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j0);
-                    float h1 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j1);
-                    float h2 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j2);
-                    float h3 = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], j3);
-                    v0 = fmaf(h0, r0.x, v0); v1 = fmaf(h0, r0.y, v1);
-                    v0 = fmaf(h1, r1.x, v0); v1 = fmaf(h1, r1.y, v1);
-                    v0 = fmaf(h2, r2.x, v0); v1 = fmaf(h2, r2.y, v1);
-                    v0 = fmaf(h3, r3.x, v0); v1 = fmaf(h3, r3.y, v1);
-                }
-                while (mask) {
-                    int jl = __ffsll((unsigned long long)mask) - 1;
-                    mask &= mask - 1;
-                    float hf = (float)(uint32_t)__builtin_amdgcn_readlane((int)hv[chunk], jl);
-                    float2 row = rows[jl * 64];
-                    v0 = fmaf(hf, row.x, v0);
-                    v1 = fmaf(hf, row.y, v1);
-                }
+            int i = 0;
+            for (; i + 4 <= nnz; i += 4) {                           // rows of four bins in flight, fmas in order
+                const int j0 = lst_j[wave][i], j1 = lst_j[wave][i + 1], j2 = lst_j[wave][i + 2],
+                          j3 = lst_j[wave][i + 3];
+                const float h0 = lst_h[wave][i], h1 = lst_h[wave][i + 1], h2 = lst_h[wave][i + 2],
+                            h3 = lst_h[wave][i + 3];
+                const float2 r0 = At2[j0 * 64 + lane], r1 = At2[j1 * 64 + lane], r2 = At2[j2 * 64 + lane],
+                             r3 = At2[j3 * 64 + lane];
+                v0 = fmaf(h0, r0.x, v0); v1 = fmaf(h0, r0.y, v1);
+                v0 = fmaf(h1, r1.x, v0); v1 = fmaf(h1, r1.y, v1);
+                v0 = fmaf(h2, r2.x, v0); v1 = fmaf(h2, r2.y, v1);
+                v0 = fmaf(h3, r3.x, v0); v1 = fmaf(h3, r3.y, v1);
+            }
+            for (; i < nnz; ++i) {
+                const int j = lst_j[wave][i];
+                const float hf = lst_h[wave][i];
+                const float2 row = At2[j * 64 + lane];
+                v0 = fmaf(hf, row.x, v0);
+                v1 = fmaf(hf, row.y, v1);
             }
             float b = INFINITY;
             int bi = IDX_NONE;
