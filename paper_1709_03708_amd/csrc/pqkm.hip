@@ -155,9 +155,23 @@ void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntile
                        ntiles, assign, dist);
 }
 
+template <int M, int R, int THREADS>
+void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                      hipStream_t st)
+{
+    constexpr int C = (THREADS / (128 / M / 4)) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan_skew_kernel<M, R, THREADS>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
+                       img, ntiles, assign, dist);
+}
+
 // the subspace-skewed scans read an x-major tile image
 // (variant 0, the default for M = 4, is the skewed scan with 16 codes per lane-slot and 1024 threads)
-inline bool variant_xmajor(int M, int variant) { return M == 4 && (variant == 0 || (variant >= 30 && variant <= 39)); }
+inline bool variant_xmajor(int M, int variant)
+{
+    if (M == 4) return variant == 0 || (variant >= 30 && variant <= 39);
+    return variant != 1;          // M = 8, 16, 32: every shape but 1 (the unskewed tiled scan) is skewed
+}
 
 template <int M>
 void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
@@ -210,22 +224,42 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
     }
 }
 template <>
-void launch_scan_M<8>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                       float* dist, hipStream_t st)
 {
-    launch_scan<8, 8, 512, false>(codes, N, img, ntiles, assign, dist, st);
+    switch (variant) {
+        case 1: launch_scan<8, 8, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 2: launch_scan_skew<8, 6, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 3: launch_scan_skew<8, 12, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 4: launch_scan_skew<8, 16, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 5: launch_scan_skew<8, 24, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        default: launch_scan_skew<8, 8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+    }
 }
 template <>
-void launch_scan_M<16>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+void launch_scan_M<16>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                        float* dist, hipStream_t st)
 {
-    launch_scan<16, 4, 512, false>(codes, N, img, ntiles, assign, dist, st);
+    switch (variant) {
+        case 1: launch_scan<16, 4, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 2: launch_scan_skew<16, 3, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 3: launch_scan_skew<16, 6, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 4: launch_scan_skew<16, 10, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        default: launch_scan_skew<16, 4, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+    }
 }
 template <>
-void launch_scan_M<32>(int, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
+void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                        float* dist, hipStream_t st)
 {
-    launch_scan<32, 2, 512, false>(codes, N, img, ntiles, assign, dist, st);
+    switch (variant) {
+        case 1: launch_scan<32, 2, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
+        case 2: launch_scan_skew<32, 1, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 3: launch_scan_skew<32, 4, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 4: launch_scan_skew<32, 6, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 5: launch_scan_skew<32, 8, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        default: launch_scan_skew<32, 2, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+    }
 }
 
 template <int M>

@@ -858,6 +858,166 @@ __global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
+// Subspace-skewed scan for M = 8, 16, 32 (64-bit SIFT-like codes, CNN-feature codes; Sec. 4).
+//
+// All M subspaces of TK = 128/M centers are resident (x-major image: row (x, m) of TK*4 bytes at
+// byte x*512 + m*TK*4), LPS = TK/4 lanes form a slot and each lane reads one 16-byte piece of
+// its code's row per step.  A 16-lane LDS access group holds SL = 16/LPS slots; slot j of the
+// group runs j subspaces behind (it reads m = i - j in step i), so the SL rows of one access sit
+// at SL different 16*LPS-byte positions of the 256-byte bank line: no conflicts.  Steps in which
+// a slot has no subspace (i < j or i >= M + j) read a line of -0.0 after the tile; the sum is a
+// chain over all M + SL - 1 steps, and since x + (-0.0) = x bit for bit its value is exactly
+// the ascending-m fp32 sum of Eq. 3.  The skew costs (SL-1)/M extra steps.
+// Per code and lane the pre-scaled offsets of all steps are kept as 16-bit fields (unpacked by
+// one SDWA shift per read); minimum tracking, prefetch of the next tile and the epilogue are
+// those of the M = 4 kernels (the epilogue rebuilds its offsets from the code bytes).
+// ---------------------------------------------------------------------------------------------
+template <int M, int R, int THREADS>
+__global__ __launch_bounds__(THREADS) void assign_scan_skew_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                   const float4* __restrict__ img, int ntiles,
+                                                                   int32_t* __restrict__ assign,
+                                                                   float* __restrict__ dist)
+{
+    constexpr int TK = 128 / M, LPS = TK / 4, SL = 16 / LPS, STEPS = M + SL - 1;
+    constexpr int RQ = LPS;                   // row size in 16-byte units
+    constexpr int NFW = (STEPS + 1) / 2;      // registers of packed offsets per code
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr uint32_t PAD = TILE_BYTES;
+    static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+
+    __shared__ float4 tile[TILE_F4 + 16];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const int j = c % SL;                     // this slot runs j subspaces behind
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
+
+    uint32_t fld[R][NFW];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        const uint8_t* x = codes + n * M;
+#pragma unroll
+        for (int w = 0; w < NFW; ++w) fld[r][w] = 0u;
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
+            const int mm = i - j;
+            const bool real = mm >= 0 && mm < M;
+            const uint32_t xv = real ? (uint32_t)x[mm] : 0u;
+            const uint32_t pos = (uint32_t)((mm + SL) % SL);                    // bank position of the row
+            const uint32_t f = real ? (xv * 32u + (uint32_t)mm * RQ + (uint32_t)q)
+                                    : ((PAD >> 4) + pos * RQ + (uint32_t)q);
+            fld[r][i / 2] |= (i & 1) ? (f << 16) : f;
+        }
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    auto issue = [&](int r, int i) -> float4 {
+        const uint32_t ad = (i & 1) ? sdwa_shl_word1(four, fld[r][i / 2]) : sdwa_shl_word0(four, fld[r][i / 2]);
+        return lds_read16(tb, ad);
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        {
+            const int tn = t + 1 < ntiles ? t + 1 : t;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
+        }
+        float4 cur = issue(0, 0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float4 sa;
+#pragma unroll
+            for (int i = 0; i < STEPS; ++i) {
+                float4 nxt = cur;
+                if (i + 1 < STEPS) nxt = issue(r, i + 1);
+                else if (r + 1 < R) nxt = issue(r + 1, 0);
+                if (i == 0) {
+                    sa = cur;
+                } else {
+                    sa.x = sa.x + cur.x; sa.y = sa.y + cur.y; sa.z = sa.z + cur.z; sa.w = sa.w + cur.w;
+                }
+                cur = nxt;
+            }
+            float m4 = __builtin_fminf(__builtin_fminf(sa.x, sa.y), sa.z);
+            m4 = __builtin_fminf(m4, sa.w);
+            tix[r] = (m4 < best[r]) ? t : tix[r];
+            best[r] = __builtin_fminf(best[r], m4);
+        }
+    }
+
+    // Epilogue: the lanes holding their slot's minimum re-read their 4 sums in the winning tile from
+    // the image (offsets rebuilt from the code bytes), pick the first center attaining the minimum,
+    // and the slot's lanes are merged by (value, index).
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; ++r0) {
+        float b = INFINITY;
+        int tx = -1;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r == r0) { b = best[r]; tx = tix[r]; }
+        float smin = b;
+#pragma unroll
+        for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+        const bool need = tx >= 0 && b == smin;
+        int bi = IDX_NONE;
+        float bv = INFINITY;
+        int64_t n = base + (int64_t)r0 * SLOTS + c;
+        if (need) {
+            const int64_t nn = n < N ? n : N - 1;
+            const uint8_t* x = codes + nn * M;
+            const char* gbase = reinterpret_cast<const char*>(img + (size_t)tx * TILE_F4);
+            v4f sv = *reinterpret_cast<const v4f*>(gbase + (uint32_t)x[0] * 512u + (uint32_t)q * 16u);
+#pragma unroll 4
+            for (int m = 1; m < M; ++m)
+                sv = sv + *reinterpret_cast<const v4f*>(gbase + (uint32_t)x[m] * 512u + (uint32_t)(m * RQ + q) * 16u);
+            const int kb = tx * TK + q * 4;
+            bv = b;
+            if (sv.w == b) { bi = kb + 3; bv = sv.w; }
+            if (sv.z == b) { bi = kb + 2; bv = sv.z; }
+            if (sv.y == b) { bi = kb + 1; bv = sv.y; }
+            if (sv.x == b) { bi = kb; bv = sv.x; }
+        }
+#pragma unroll
+        for (int d = LPS / 2; d >= 1; d >>= 1) {
+            float ob = __shfl_xor(bv, d);
+            int oi = __shfl_xor(bi, d);
+            if (ob < bv || (ob == bv && oi < bi)) { bv = ob; bi = oi; }
+        }
+        if (q == 0 && n < N) {
+            assign[n] = (bi == IDX_NONE) ? 0 : bi;
+            if (dist) dist[n] = bv;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Zero fill (a kernel, not a memset node, so that callers may capture the calls in a graph).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)

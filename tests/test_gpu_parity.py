@@ -98,7 +98,20 @@ def test_assign_every_compiled_shape(env, variant):
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
 
 
-@pytest.mark.parametrize("M", [4, 8, 5])
+@pytest.mark.parametrize("M,variant", [(8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (16, 1), (16, 2), (16, 3), (16, 4),
+                                       (32, 1), (32, 2), (32, 3), (32, 4), (32, 5)])
+def test_assign_every_compiled_shape_wide_codes(env, M, variant):
+    w = workload(1, M=M, D=16 * M, N=7001, K=77, T=40)
+    W = env["W"]
+    codes = W.codes_numpy(w)
+    centers = codes[W.init_center_indices(w)].copy()
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+    rng = np.random.default_rng(M + variant)
+    _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=2, scan_variant=variant)
+
+
+@pytest.mark.parametrize("M", [4, 8, 5, 16, 32])
 def test_assign_ties_go_to_lowest_index(env, M):
     """Hamming tables: massive ties, in and across tiles and lanes."""
     rng = np.random.default_rng(7)
