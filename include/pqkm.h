@@ -113,6 +113,36 @@ pqkm_status pqkm_fit(const uint8_t *codes, int64_t N, int32_t M, const float *ta
                      uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Alg. 1 with a stop condition (Sec. 3.3: "any condition can be adopted"): iterate
+ * { pqkm_assign ; pqkm_update } until an assignment step changes no assignment, or max_iters.
+ * Per iteration the library reports, to HOST memory:
+ *   objective     sum over n of the squared symmetric distance found by the assignment step
+ *                 (Eq. 4 with the squared distance), accumulated in fp64 in a fixed tree order
+ *   changed       number of codes whose assignment differs from the previous iteration's
+ *                 (the first iteration reports N)
+ *   nonzero_bins  non-zero histogram bins over all centers and subspaces (the ||h||_0 of Tab. 3, summed)
+ *   nonempty      centers with at least one member
+ * This is the one method entry point that BLOCKS: it synchronises `stream` once per iteration to
+ * read those four numbers back.  centers / assign / hist / counts as in pqkm_fit.
+ *   stats       host, [max_iters], out, may be NULL
+ *   iters_done  host, out, may be NULL
+ * Needs pqkm_fit_until_workspace_bytes(N, M, K) of workspace (the pqkm_fit workspace plus 8 bytes per
+ * code for the previous assignment and the distances).
+ */
+typedef struct {
+    double objective;
+    int64_t changed;
+    int64_t nonzero_bins;
+    int64_t nonempty;
+} pqkm_iter_stats;
+
+size_t pqkm_fit_until_workspace_bytes(int64_t N, int32_t M, int32_t K);
+pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const float *tables, int32_t K,
+                           uint8_t *centers, int32_t max_iters, int32_t *assign, uint32_t *hist,
+                           uint32_t *counts, pqkm_iter_stats *stats, int32_t *iters_done,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tuning and measurement hooks (not part of the method).
  *
  * pqkm_set_option: process-wide integer knobs, by name (host string).  Unknown

@@ -52,6 +52,8 @@ def _load():
         lib.pqko_objective.argtypes = [vp, i64, i32, vp, vp, vp]
         lib.pqko_objective.restype = ctypes.c_double
         lib.pqko_fit.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp]
+        lib.pqko_fit_until.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp]
+        lib.pqko_fit_until.restype = ctypes.c_int
         for name in ("pqko_set_threads", "pqko_build_tables", "pqko_decode", "pqko_sdc_pairs",
                      "pqko_assign", "pqko_histogram", "pqko_vote", "pqko_update",
                      "pqko_update_naive", "pqko_fit"):
@@ -201,3 +203,21 @@ def fit(codes, tables, centers, iters: int):
     counts = np.zeros(K, dtype=np.uint32)
     _load().pqko_fit(_p(codes), N, M, _p(tables), K, _p(out), int(iters), _p(a), _p(hist), _p(counts))
     return out, a, hist, counts
+
+
+def fit_until(codes, tables, centers, max_iters: int):
+    """Alg. 1 until no assignment changes (or max_iters):
+    -> (centers, assign, hist, counts, stats [iters][4] = objective, changed, nonzero bins, nonempty clusters)."""
+    tables = _chk(tables, np.float32)
+    M = tables.shape[0]
+    codes = _chk(codes, np.uint8)
+    N = codes.shape[0]
+    out = _chk(centers, np.uint8).copy()
+    K = out.shape[0]
+    a = np.zeros(N, dtype=np.int32)
+    hist = np.zeros((K, M, L), dtype=np.uint32)
+    counts = np.zeros(K, dtype=np.uint32)
+    stats = np.zeros((max(int(max_iters), 1), 4), dtype=np.float64)
+    it = _load().pqko_fit_until(_p(codes), N, M, _p(tables), K, _p(out), int(max_iters), _p(a), _p(hist),
+                                _p(counts), _p(stats))
+    return out, a, hist, counts, stats[:it].copy()

@@ -259,3 +259,46 @@ void pqko_fit(const uint8_t *codes, int64_t N, int M, const float *tables, int K
         pqko_update(codes, N, M, assign, K, tables, centers, hist, counts);
     }
 }
+
+/*
+ * Alg. 1 with a stop condition ("any condition can be adopted", Sec. 3.3): stop after the iteration in
+ * which the assignment step changed no assignment (the fixed point of the loop), or after max_iters.
+ * Per iteration it, four statistics are recorded (layout [max_iters][4] doubles):
+ *   0: objective  = sum over n of the squared SD of the assignment step (fp64 sum of the fp32 minima,
+ *                   ascending n) -- Eq. 4 with the squared distance
+ *   1: changed    = #{ n : a_it(n) != a_{it-1}(n) }, with a_{-1}(n) = -1 (so iteration 0 reports N)
+ *   2: nonzero    = number of non-zero histogram bins over all (k, m) (the ||h||_0 of Tab. 3, summed)
+ *   3: nonempty   = number of clusters with at least one member
+ * Returns the number of iterations done.  centers / assign / hist / counts as in pqko_fit.
+ */
+int pqko_fit_until(const uint8_t *codes, int64_t N, int M, const float *tables, int K, uint8_t *centers,
+                   int max_iters, int32_t *assign, uint32_t *hist, uint32_t *counts, double *stats)
+{
+    int32_t *prev = (int32_t *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int32_t));
+    float *dist = (float *)malloc((size_t)(N > 0 ? N : 1) * sizeof(float));
+    for (int64_t n = 0; n < N; ++n) prev[n] = -1;
+    int it = 0;
+    while (it < max_iters) {
+        pqko_assign(codes, N, M, centers, K, tables, assign, dist);
+        double obj = 0.0;
+        int64_t changed = 0;
+        for (int64_t n = 0; n < N; ++n) {
+            obj += (double)dist[n];
+            if (assign[n] != prev[n]) changed += 1;
+            prev[n] = assign[n];
+        }
+        pqko_update(codes, N, M, assign, K, tables, centers, hist, counts);
+        int64_t nz = 0, ne = 0;
+        for (size_t i = 0; i < (size_t)K * M * PQKO_L; ++i) nz += hist[i] != 0;
+        for (int k = 0; k < K; ++k) ne += counts[k] != 0;
+        stats[4 * it + 0] = obj;
+        stats[4 * it + 1] = (double)changed;
+        stats[4 * it + 2] = (double)nz;
+        stats[4 * it + 3] = (double)ne;
+        ++it;
+        if (changed == 0) break;
+    }
+    free(prev);
+    free(dist);
+    return it;
+}

@@ -36,9 +36,12 @@ def load():
         lib.pqkm_assign.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.pqkm_update.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.pqkm_fit.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.pqkm_fit_until_workspace_bytes.restype = sz
+        lib.pqkm_fit_until_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.pqkm_fit_until.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
-        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_set_option",
+        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
                   "pqkm_profile_read"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -162,6 +165,43 @@ def fit(codes, tables, centers, iters, assign=None, hist=None, counts=None, work
     _check(load().pqkm_fit(_ptr(codes), N, M, _ptr(tables), K, _ptr(centers), int(iters), _ptr(assign), _ptr(hist),
                            _ptr(counts), _ptr(workspace), wb, _stream()), "pqkm_fit")
     return centers, assign
+
+
+class IterStats(ctypes.Structure):
+    _fields_ = [("objective", ctypes.c_double), ("changed", ctypes.c_int64), ("nonzero_bins", ctypes.c_int64),
+                ("nonempty", ctypes.c_int64)]
+
+
+def fit_until_workspace_bytes(N: int, M: int, K: int) -> int:
+    return int(load().pqkm_fit_until_workspace_bytes(int(N), int(M), int(K)))
+
+
+def fit_until(codes, tables, centers, max_iters, assign=None, hist=None, counts=None, workspace=None):
+    """Iterates in place on ``centers`` until no assignment changes (blocks once per iteration);
+    -> (centers, assign, list of (objective, changed, nonzero_bins, nonempty) per iteration)."""
+    import torch
+
+    N, M = codes.shape
+    K = centers.shape[0]
+    _need(codes, torch.uint8, (N, M), "codes")
+    _need(centers, torch.uint8, (K, M), "centers")
+    _need(tables, torch.float32, (M, L, L), "tables")
+    if assign is None:
+        assign = torch.empty(N, dtype=torch.int32, device=codes.device)
+    _need(assign, torch.int32, (N,), "assign")
+    _need(hist, torch.int32, (K, M, L), "hist")
+    _need(counts, torch.int32, (K,), "counts")
+    need = fit_until_workspace_bytes(N, M, K)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=codes.device)
+    stats = (IterStats * max(int(max_iters), 1))()
+    done = ctypes.c_int32(0)
+    _check(load().pqkm_fit_until(_ptr(codes), N, M, _ptr(tables), K, _ptr(centers), int(max_iters), _ptr(assign),
+                                 _ptr(hist), _ptr(counts), ctypes.cast(stats, ctypes.c_void_p), ctypes.cast(
+                                     ctypes.pointer(done), ctypes.c_void_p), _ptr(workspace), workspace.numel(),
+                                 _stream()), "pqkm_fit_until")
+    out = [(stats[i].objective, stats[i].changed, stats[i].nonzero_bins, stats[i].nonempty) for i in range(done.value)]
+    return centers, assign, out
 
 
 def set_option(name: str, value: int) -> None:

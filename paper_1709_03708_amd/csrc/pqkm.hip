@@ -459,6 +459,80 @@ pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* ta
     return PQKM_OK;
 }
 
+// extra workspace of pqkm_fit_until, placed after the pqkm_fit carve
+struct UntilCarve { size_t prev_off, dist_off, pa_off, ph_off, out_off, total; };
+
+static UntilCarve until_carve(int64_t N, int M, int K)
+{
+    UntilCarve u{};
+    size_t off = carve(N, M, K).total;
+    u.prev_off = off;  off += align256((size_t)N * sizeof(int32_t));
+    u.dist_off = off;  off += align256((size_t)N * sizeof(float));
+    u.pa_off = off;    off += align256((size_t)STAT_BLOCKS * sizeof(StatPartial));
+    u.ph_off = off;    off += align256((size_t)STAT_BLOCKS * sizeof(StatPartial));
+    u.out_off = off;   off += 256;
+    u.total = off;
+    return u;
+}
+
+size_t pqkm_fit_until_workspace_bytes(int64_t N, int32_t M, int32_t K)
+{
+    if (!shape_ok(N, M, K)) return 0;
+    return until_carve(N, M, K).total;
+}
+
+pqkm_status pqkm_fit_until(const uint8_t* codes, int64_t N, int32_t M, const float* tables, int32_t K,
+                           uint8_t* centers, int32_t max_iters, int32_t* assign, uint32_t* hist, uint32_t* counts,
+                           pqkm_iter_stats* stats, int32_t* iters_done, void* workspace, size_t workspace_bytes,
+                           void* stream)
+{
+    if (!shape_ok(N, M, K) || max_iters < 0) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    const UntilCarve u = until_carve(N, M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, u.total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    const Carve c = carve(N, M, K);
+    int32_t* prev = reinterpret_cast<int32_t*>(ws + u.prev_off);
+    float* dist = reinterpret_cast<float*>(ws + u.dist_off);
+    StatPartial* pa = reinterpret_cast<StatPartial*>(ws + u.pa_off);
+    StatPartial* ph = reinterpret_cast<StatPartial*>(ws + u.ph_off);
+    unsigned long long* out = reinterpret_cast<unsigned long long*>(ws + u.out_off);
+    if (!hist) hist = reinterpret_cast<uint32_t*>(ws + c.hist_off);
+    if (!counts) counts = reinterpret_cast<uint32_t*>(ws + c.counts_off);
+    if (iters_done) *iters_done = 0;
+    if (N > 0) {
+        unsigned fb = (unsigned)((N + 255) / 256 < 65536 ? (N + 255) / 256 : 65536);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(fb), dim3(256), 0, st, prev, N, (int32_t)-1);
+    }
+    for (int it = 0; it < max_iters; ++it) {
+        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st);
+        if (s != PQKM_OK) return s;
+        hipLaunchKernelGGL(iter_assign_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, assign, prev, dist, N, pa);
+        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, st);
+        if (s != PQKM_OK) return s;
+        hipLaunchKernelGGL(iter_hist_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, hist, (int64_t)K * M * L,
+                           counts, K, ph);
+        hipLaunchKernelGGL(iter_stats_final_kernel, dim3(1), dim3(64), 0, st, pa, ph, out);
+        unsigned long long h[4];
+        if (hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, st) != hipSuccess) return PQKM_ERR_DEVICE;
+        if (hipStreamSynchronize(st) != hipSuccess) return PQKM_ERR_DEVICE;
+        if (stats) {
+            double d;
+            memcpy(&d, &h[0], sizeof(d));
+            stats[it].objective = d;
+            stats[it].changed = (int64_t)h[1];
+            stats[it].nonzero_bins = (int64_t)h[2];
+            stats[it].nonempty = (int64_t)h[3];
+        }
+        if (iters_done) *iters_done = it + 1;
+        if (h[1] == 0) break;
+    }
+    return PQKM_OK;
+}
+
 pqkm_status pqkm_set_option(const char* name, int32_t value)
 {
     if (!name) return PQKM_ERR_NULL;

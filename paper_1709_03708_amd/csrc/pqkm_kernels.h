@@ -1339,4 +1339,98 @@ __global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist,
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Per-iteration statistics of the convergence-checked loop (Alg. 1 with a stop condition).
+// All reductions run in a fixed order (per-lane strided sums, xor-shuffle tree, per-block partials
+// summed by one wave), so the fp64 objective is reproducible from run to run.
+// ---------------------------------------------------------------------------------------------
+constexpr int STAT_BLOCKS = 1024;
+
+struct StatPartial { double dsum; unsigned long long cnt_a; unsigned long long cnt_b; };
+
+__device__ __forceinline__ void stat_block_reduce(double d, unsigned long long a, unsigned long long b,
+                                                  StatPartial* out)
+{
+    __shared__ StatPartial sm[4];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        d += __shfl_xor(d, o);
+        a += __shfl_xor(a, o);
+        b += __shfl_xor(b, o);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sm[wave].dsum = d; sm[wave].cnt_a = a; sm[wave].cnt_b = b; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        StatPartial r = sm[0];
+        for (int w = 1; w < 4; ++w) { r.dsum += sm[w].dsum; r.cnt_a += sm[w].cnt_a; r.cnt_b += sm[w].cnt_b; }
+        *out = r;
+    }
+}
+
+// objective and number of changed assignments; also moves the new assignment into `prev`
+__global__ __launch_bounds__(256) void iter_assign_stats_kernel(const int32_t* __restrict__ assign,
+                                                                int32_t* __restrict__ prev,
+                                                                const float* __restrict__ dist, int64_t N,
+                                                                StatPartial* __restrict__ partial)
+{
+    double d = 0.0;
+    unsigned long long changed = 0;
+    for (int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x; n < N; n += (int64_t)STAT_BLOCKS * 256) {
+        const int32_t a = assign[n];
+        d += (double)dist[n];
+        changed += (a != prev[n]);
+        prev[n] = a;
+    }
+    stat_block_reduce(d, changed, 0ull, partial + blockIdx.x);
+}
+
+// non-zero histogram bins and non-empty clusters
+__global__ __launch_bounds__(256) void iter_hist_stats_kernel(const uint32_t* __restrict__ hist, int64_t nbins,
+                                                              const uint32_t* __restrict__ counts, int K,
+                                                              StatPartial* __restrict__ partial)
+{
+    unsigned long long nz = 0, ne = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nbins; i += (int64_t)STAT_BLOCKS * 256)
+        nz += (hist[i] != 0u);
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < K; k += (int64_t)STAT_BLOCKS * 256)
+        ne += (counts[k] != 0u);
+    stat_block_reduce(0.0, nz, ne, partial + blockIdx.x);
+}
+
+// out[0] = objective (as double bits), out[1] = changed, out[2] = nonzero bins, out[3] = nonempty
+__global__ __launch_bounds__(64) void iter_stats_final_kernel(const StatPartial* __restrict__ pa,
+                                                              const StatPartial* __restrict__ ph,
+                                                              unsigned long long* __restrict__ out)
+{
+    double d = 0.0;
+    unsigned long long ch = 0, nz = 0, ne = 0;
+    for (int i = threadIdx.x; i < STAT_BLOCKS; i += 64) {
+        d += pa[i].dsum;
+        ch += pa[i].cnt_a;
+        nz += ph[i].cnt_a;
+        ne += ph[i].cnt_b;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        d += __shfl_xor(d, o);
+        ch += __shfl_xor(ch, o);
+        nz += __shfl_xor(nz, o);
+        ne += __shfl_xor(ne, o);
+    }
+    if (threadIdx.x == 0) {
+        out[0] = (unsigned long long)__double_as_longlong(d);
+        out[1] = ch;
+        out[2] = nz;
+        out[3] = ne;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n; i += stride) p[i] = v;
+}
+
 }  // namespace pqkm

@@ -256,6 +256,42 @@ def test_config2_sift32_all_iterations(env):
     _run_config_full(env, 2, workload(2).iters)
 
 
+@pytest.mark.parametrize("cfg,over", [(1, {}), (2, dict(N=200_000, K=300, T=600)), (3, dict(N=50_000, K=200, T=300))])
+def test_fit_until_matches_oracle(env, cfg, over):
+    """Alg. 1 with the stop condition: same number of iterations, integer statistics exact, the fp64
+    objective within 1e-9 relative (it is a sum of N fp32 terms in a different order: error <= N * 2^-53),
+    final centers / assignment / histogram bit-exact."""
+    pq, oracle, W = env["pq"], env["oracle"], env["W"]
+    w = workload(cfg, **over)
+    codes = W.codes_numpy(w)
+    cent0 = codes[W.init_center_indices(w)].copy()
+    tables = oracle.build_tables(W.codewords(w))
+    d_cent = _dev(env, cent0)
+    torch = env["torch"]
+    hist = torch.empty((w.K, w.M, 256), dtype=torch.int32, device=env["dev"])
+    counts = torch.empty(w.K, dtype=torch.int32, device=env["dev"])
+    _, a, stats = pq.fit_until(_dev(env, codes), _dev(env, tables), d_cent, 40, hist=hist, counts=counts)
+    _sync(env)
+    rc, ra, rh, rcnt, rstats = oracle.fit_until(codes, tables, cent0, 40)
+    assert len(stats) == len(rstats) and 2 <= len(stats) < 40
+    for (obj, ch, nz, ne), r in zip(stats, rstats):
+        assert abs(obj - r[0]) <= 1e-9 * r[0]
+        assert (ch, nz, ne) == (int(r[1]), int(r[2]), int(r[3]))
+    assert stats[-1][1] == 0
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+    np.testing.assert_array_equal(a.cpu().numpy(), ra)
+    np.testing.assert_array_equal(u32(hist), rh)
+    np.testing.assert_array_equal(u32(counts), rcnt)
+    # the cap is honoured, and zero iterations touch nothing
+    d2 = _dev(env, cent0)
+    _, _, s2 = pq.fit_until(_dev(env, codes), _dev(env, tables), d2, 2)
+    assert len(s2) == 2 and s2[1][1] == int(rstats[1][1])
+    d3 = _dev(env, cent0)
+    _, _, s3 = pq.fit_until(_dev(env, codes), _dev(env, tables), d3, 0)
+    _sync(env)
+    assert s3 == [] and (d3.cpu().numpy() == cent0).all()
+
+
 def _run_config_sampled(env, cfg, n_sample, iters=1):
     """Full-size run in the launch configuration the benchmark uses.  The assignment is checked
     on a seeded sample of codes against all K centers; histogram, counts and vote are checked in

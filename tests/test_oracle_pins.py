@@ -431,3 +431,33 @@ def test_oracle_reproduces_the_stored_config1_run():
     assert make_golden.compute() == stored
     objs = [float(l.split()[3]) for l in stored if l.startswith("iter")]
     assert all(b <= a for a, b in zip(objs, objs[1:])) and len(objs) == 5
+
+
+def test_fit_until_stops_at_the_fixed_point_and_reports_statistics(small_problem):
+    """Alg. 1 with the stop condition 'no assignment changed' (Sec. 3.3 allows any condition).
+    Pinned against a hand-rolled loop over the already pinned assign/update, numpy for the
+    statistics, and the fixed-point property: one more iteration changes nothing."""
+    codes, centers, tables = small_problem["codes"], small_problem["centers"], small_problem["tables"]
+    fc, fa, fh, fcnt, stats = oracle.fit_until(codes, tables, centers, 50)
+    iters = len(stats)
+    assert 2 <= iters < 50                      # converges well before the cap on this problem
+    cent = centers.copy()
+    prev = np.full(len(codes), -1, np.int32)
+    for it in range(iters):
+        a, d = oracle.assign(codes, cent, tables)
+        assert abs(stats[it, 0] - d.astype(np.float64).sum()) <= 1e-12 * stats[it, 0]
+        assert stats[it, 1] == (a != prev).sum()
+        cent, h, cnt = oracle.update(codes, a, tables, cent)
+        assert stats[it, 2] == (h != 0).sum() and stats[it, 3] == (cnt != 0).sum()
+        prev = a
+    assert stats[0, 1] == len(codes) and stats[-1, 1] == 0 and (stats[:-1, 1] > 0).all()
+    assert (np.diff(stats[:, 0]) <= 1e-9 * stats[0, 0]).all()             # Lloyd: the objective never increases
+    np.testing.assert_array_equal(fc, cent)
+    np.testing.assert_array_equal(fa, prev)
+    # fixed point: another assignment against the final centers reproduces the assignment and the centers
+    a2, _ = oracle.assign(codes, fc, tables)
+    np.testing.assert_array_equal(a2, fa)
+    np.testing.assert_array_equal(oracle.update(codes, a2, tables, fc)[0], fc)
+    # the cap is honoured
+    _, _, _, _, s2 = oracle.fit_until(codes, tables, centers, 2)
+    assert len(s2) == 2 and (s2 == stats[:2]).all()
