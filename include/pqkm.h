@@ -113,7 +113,7 @@ pqkm_status pqkm_fit(const uint8_t *codes, int64_t N, int32_t M, const float *ta
                      uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Alg. 1 with a stop condition (Sec. 3.3: "any condition can be adopted"): iterate
+ * Alg. 1 with a stop condition (Sec. 3.3 leaves the stop rule of the loop open): iterate
  * { pqkm_assign ; pqkm_update } until an assignment step changes no assignment, or max_iters.
  * Per iteration the library reports, to HOST memory:
  *   objective     sum over n of the squared symmetric distance found by the assignment step
@@ -150,7 +150,7 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
  *   "assign_kernel"      0 = choose automatically (default), 1 = force the generic
  *                        scan that reads the tables through the cache hierarchy,
  *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
- *   "scan_variant"       0 = default launch shape of the LDS-tiled scan, 1..64 =
+ *   "scan_variant"       0 = default launch shape of the LDS-tiled scan, 1..99 =
  *                        one specific compiled shape (for tuning sweeps)
  *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
  *                        per code and subspace, 2 = force the LDS-privatised histogram

@@ -35,8 +35,12 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, total;
+        gid_bytes, gco_off, plan_off, total;
 };
+
+// The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
+constexpr int64_t GROUP_CHUNK_MAX = (int64_t)1 << 26;
+inline int64_t group_alloc(int64_t n) { return (n + 14) & ~(int64_t)7; }   // regrouped positions for n codes
 
 // Shape of the LDS-privatised histogram pass: KT clusters per workgroup, `groups` cluster groups, S code slices.
 struct HistPlan { int KT; int64_t groups; int S; bool cheap; };
@@ -82,6 +86,14 @@ Carve carve(int64_t N, int M, int K)
     c.gid_off = off;
     c.gid_bytes = (hp.KT >= 1 && hp.groups <= 255) ? (size_t)N : 0;
     off += align256(c.gid_bytes);
+    c.gco_off = c.plan_off = off;
+    if (M == 4) {
+        const int64_t na = group_alloc(N < GROUP_CHUNK_MAX ? N : GROUP_CHUNK_MAX);
+        c.gco_off = off;
+        off += align256((size_t)na * sizeof(uint2));
+        c.plan_off = off;
+        off += align256(sizeof(GroupPlan));
+    }
     c.total = off;
     return c;
 }
@@ -155,6 +167,36 @@ void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntile
                        ntiles, assign, dist);
 }
 
+template <int R, int THREADS, int DEPTH>
+void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, int ntiles,
+                   int32_t* assign, float* dist, hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, gco,
+                       img, ntiles, assign, dist);
+}
+
+template <int R, int THREADS, int DEPTH>
+void launch_scan4q(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, int ntiles,
+                   int32_t* assign, float* dist, hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4q_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
+                       gco, img, ntiles, assign, dist);
+}
+
+template <int R, int THREADS>
+void launch_scan4sd(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
+                    hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4sd_kernel<R, THREADS>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, img,
+                       ntiles, assign, dist);
+}
+
 template <int M, int R, int THREADS>
 void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
                       hipStream_t st)
@@ -165,17 +207,49 @@ void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int nt
                        img, ntiles, assign, dist);
 }
 
-// the subspace-skewed scans read an x-major tile image
-// (variant 0, the default for M = 4, is the skewed scan with 16 codes per lane-slot and 1024 threads)
-inline bool variant_xmajor(int M, int variant)
+// tile image layout a scan shape reads: 0 = [m][x][k], 1 = [x][m][k] (subspace-skewed scans), 2 = half planes
+// (variant 0, the default for M = 4, regroups the codes and runs the half-plane scan; variant 34 is the
+// subspace-skewed scan, which needs no regrouping and is used for few centers or few codes)
+inline int variant_layout(int M, int variant)
 {
-    if (M == 4) return variant == 0 || (variant >= 30 && variant <= 39);
-    return variant != 1;          // M = 8, 16, 32: every shape but 1 (the unskewed tiled scan) is skewed
+    if (M == 4) {
+        if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79)) return 2;
+        if (variant >= 50 && variant <= 59) return 3;     // [m][x][k] with 16-center tiles
+        return (variant == 0 || (variant >= 30 && variant <= 39) || (variant >= 60 && variant <= 69)) ? 1 : 0;
+    }
+    return variant != 1 ? 1 : 0;  // M = 8, 16, 32: every shape but 1 (the unskewed tiled scan) is skewed
 }
 
 template <int M>
 void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
                    float* dist, hipStream_t st);
+
+// M = 4 scans over regrouped codes: variants 70..79
+void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
+                         float* dist, hipStream_t st)
+{
+    switch (variant) {
+        case 71: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
+        case 72: launch_scan4p<24, 512, 4>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
+        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
+        case 74: launch_scan4p<32, 512, 2>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
+        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;   // 70
+    }
+}
+
+// regroup `cnt` codes into gco: three launches on the stream
+pqkm_status regroup_codes(const uint8_t* codes, int64_t cnt, uint2* gco, GroupPlan* plan, hipStream_t st)
+{
+    const int64_t na = group_alloc(cnt);
+    int64_t g = (cnt + 4095) / 4096;
+    if (g > GROUP_MAX_WGS) g = GROUP_MAX_WGS;
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(code_class_count_kernel, dim3((unsigned)g), dim3(GROUP_THREADS), 0, st, codes, cnt, plan);
+    hipLaunchKernelGGL(code_group_plan_kernel, dim3(1), dim3(1024), 0, st, plan, (int)g);
+    hipLaunchKernelGGL(code_group_scatter_kernel, dim3((unsigned)g), dim3(GROUP_THREADS), 0, st, codes, cnt, plan, gco,
+                       na);
+    return launched();
+}
 
 template <>
 void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
@@ -220,6 +294,30 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 37: launch_scan4s<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 38: launch_scan4s<20, 768>(codes, N, img, ntiles, assign, dist, st); break;
         case 39: launch_scan4s<14, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 40: launch_scan4p<16, 1024, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 41: launch_scan4p<16, 1024, 1>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 42: launch_scan4p<8, 1024, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 43: launch_scan4p<16, 768, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 44: launch_scan4p<24, 512, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 45: launch_scan4p<32, 512, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 46: launch_scan4p<28, 512, 3>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 47: launch_scan4p<20, 768, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 48: launch_scan4p<32, 512, 3>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 49: launch_scan4p<24, 512, 6>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 50: launch_scan4q<32, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 51: launch_scan4q<16, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 52: launch_scan4q<12, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 53: launch_scan4q<32, 256, 4>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 54: launch_scan4q<48, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 55: launch_scan4q<32, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 56: launch_scan4q<16, 512, 4>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 57: launch_scan4q<16, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
+        case 60: launch_scan4sd<16, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 61: launch_scan4sd<20, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 62: launch_scan4sd<24, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 63: launch_scan4sd<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 64: launch_scan4sd<12, 768>(codes, N, img, ntiles, assign, dist, st); break;
+        case 65: launch_scan4sd<16, 768>(codes, N, img, ntiles, assign, dist, st); break;
         default: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
@@ -262,22 +360,51 @@ void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float
     }
 }
 
+// Which scan runs: for M = 4 with the default variant, the regrouped half-plane scan when there is enough work
+// to pay for regrouping (a pass over the codes) and the subspace-skewed scan otherwise.
+inline int effective_variant(int M, int variant, int64_t N, int K)
+{
+    if (M != 4 || variant != 0) return variant;
+    if (K < 128 || N < 65536) return 34;
+    const int64_t wgs28 = (N + 128 * 28 - 1) / (128 * 28);
+    return wgs28 > 2048 ? 71 : 70;       // many rounds of workgroups: 28 codes per lane-slot (no spill); else 32
+}
+inline bool variant_grouped(int M, int variant) { return M == 4 && variant >= 70 && variant <= 79; }
+
 template <int M>
 pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers, int K, const float* tables,
-                         int32_t* assign, float* dist, float* img, const Options& opt, hipStream_t st)
+                         int32_t* assign, float* dist, float* img, const Options& opt, const Carve& c, char* ws,
+                         bool reuse_groups, hipStream_t st)
 {
     constexpr int TK = 128 / M;
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
-    if (variant_xmajor(M, opt.scan_variant))
-        hipLaunchKernelGGL((tile_image_kernel<M, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+    const int variant = effective_variant(M, opt.scan_variant, N, K);
+    const int layout = variant_layout(M, variant);
+    if (layout == 3 && M == 4)
+        hipLaunchKernelGGL((tile_image_kernel<4, 0, 16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           centers, K, tables, img, total);
+    else if (layout == 2 && M == 4)
+        hipLaunchKernelGGL((tile_image_kernel<4, 2>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           centers, K, tables, img, total);
+    else if (layout == 1)
+        hipLaunchKernelGGL((tile_image_kernel<M, 1>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            centers, K, tables, img, total);
     else
-        hipLaunchKernelGGL((tile_image_kernel<M, false>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+        hipLaunchKernelGGL((tile_image_kernel<M, 0>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            centers, K, tables, img, total);
     if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
-    for (int64_t n0 = 0; n0 < N; n0 += opt.launch_codes) {
-        int64_t cnt = N - n0 < opt.launch_codes ? N - n0 : opt.launch_codes;
+    const bool grouped = variant_grouped(M, variant);
+    int64_t per_launch = opt.launch_codes;
+    if (grouped && per_launch > GROUP_CHUNK_MAX) per_launch = GROUP_CHUNK_MAX;
+    uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
+    GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
+    for (int64_t n0 = 0; n0 < N; n0 += per_launch) {
+        int64_t cnt = N - n0 < per_launch ? N - n0 : per_launch;
+        // the regrouped copy survives between calls only when one launch covers all codes
+        if (grouped && !(reuse_groups && N <= per_launch)) {
+            if (regroup_codes(codes + n0 * M, cnt, gco, plan, st) != PQKM_OK) return PQKM_ERR_DEVICE;
+        }
         EventPair ev{};
         bool prof = false;
         if (opt.profile) {
@@ -292,8 +419,12 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             }
         }
         if (prof) hipEventRecord(ev.a, st);
-        launch_scan_M<M>(opt.scan_variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), (int)ntiles,
-                         assign + n0, dist ? dist + n0 : nullptr, st);
+        if (grouped)
+            launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
+                                assign + n0, dist ? dist + n0 : nullptr, st);
+        else
+            launch_scan_M<M>(variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), (int)ntiles,
+                             assign + n0, dist ? dist + n0 : nullptr, st);
         if (prof) hipEventRecord(ev.b, st);
         if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
     }
@@ -301,7 +432,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
 }
 
 pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* centers, int K, const float* tables,
-                        int32_t* assign, float* dist, void* ws, hipStream_t st)
+                        int32_t* assign, float* dist, void* ws, hipStream_t st, bool reuse_groups = false)
 {
     if (N == 0) return PQKM_OK;
     Options opt;
@@ -318,11 +449,12 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
     }
     Carve c = carve(N, M, K);
     float* img = reinterpret_cast<float*>(static_cast<char*>(ws) + c.img_off);
+    char* wsc = static_cast<char*>(ws);
     switch (M) {
-        case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, st);
-        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, st);
-        case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, st);
-        default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, st);
+        case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
+        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
+        case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
+        default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
     }
 }
 
@@ -451,7 +583,8 @@ pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* ta
     if (s != PQKM_OK) return s;
     if ((s = check_device()) != PQKM_OK) return s;
     for (int it = 0; it < iters; ++it) {
-        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream);
+        // the codes do not change between iterations: regroup them for the scan once
+        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream, it > 0);
         if (s != PQKM_OK) return s;
         s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
         if (s != PQKM_OK) return s;
@@ -508,7 +641,7 @@ pqkm_status pqkm_fit_until(const uint8_t* codes, int64_t N, int32_t M, const flo
         hipLaunchKernelGGL(fill_i32_kernel, dim3(fb), dim3(256), 0, st, prev, N, (int32_t)-1);
     }
     for (int it = 0; it < max_iters; ++it) {
-        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st);
+        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st, it > 0);
         if (s != PQKM_OK) return s;
         hipLaunchKernelGGL(iter_assign_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, assign, prev, dist, N, pa);
         s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, st);
@@ -541,7 +674,7 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
         if (value < 0 || value > 2) return PQKM_ERR_SHAPE;
         g_opt.assign_kernel = value;
     } else if (strcmp(name, "scan_variant") == 0) {
-        if (value < 0 || value > 64) return PQKM_ERR_SHAPE;
+        if (value < 0 || value > 99) return PQKM_ERR_SHAPE;
         g_opt.scan_variant = value;
     } else if (strcmp(name, "hist_kernel") == 0) {
         if (value < 0 || value > 2) return PQKM_ERR_SHAPE;

@@ -81,19 +81,25 @@ __global__ __launch_bounds__(256) void assign_generic_kernel(const uint8_t* __re
 // subcodes rather than all on the same ones.  Centers past K are padded with +inf, which a
 // strict "<" never selects.  One thread per element, kin fastest, so stores are contiguous.
 // ---------------------------------------------------------------------------------------------
-// XMAJOR selects the alternative order img[tile][x][m][kin] used by the subspace-skewed scan, in which
-// the LDS bank half of a row is decided by the parity of m instead of the parity of x.
-template <int M, bool XMAJOR = false>
+// LAYOUT 1 is the alternative order img[tile][x][m][kin] used by the subspace-skewed scan, in which
+// the LDS bank half of a row is decided by the parity of m instead of the parity of x.  LAYOUT 2
+// (M = 4, TK = 32 only) is img[tile][m][h][x][kin % 16] with h = kin / 16: eight planes of 16 KB.
+// TK defaults to the 128 KB tile; the 16-center scan for M = 4 uses LAYOUT 0 with TK = 16 (64 KB tiles).
+template <int M, int LAYOUT = 0, int TK = 128 / M>
 __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restrict__ centers, int K,
                                                          const float* __restrict__ tables, float* __restrict__ img,
                                                          int64_t total)
 {
-    constexpr int TK = 128 / M;
     int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
     int kin = (int)(e % TK);
     int x, m;
-    if (XMAJOR) {
+    if (LAYOUT == 2) {
+        const int h = (int)((e / (16 * L)) % 2);
+        kin = (int)(e % 16) + 16 * h;
+        x = (int)((e / 16) % L);
+        m = (int)((e / (32 * L)) % M);
+    } else if (LAYOUT == 1) {
         m = (int)((e / TK) % M);
         x = (int)((e / (TK * M)) % L);
     } else {
@@ -665,6 +671,13 @@ __global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* 
 // (((V0 + V1) + V2) + V3) + V4 in which the -0.0 comes first or last.  Adding -0.0 returns the
 // other operand bit for bit, so the value is exactly ((A0 + A1) + A2) + A3 in every lane.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float min3_f32(float a, float b, float c)
+{
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 template <int R, int THREADS>
 __global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* __restrict__ codes, int64_t N,
                                                                 const float4* __restrict__ img, int ntiles,
@@ -852,6 +865,837 @@ __global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* _
             if (q == 0 && n < N) {
                 assign[n] = (bi == IDX_NONE) ? 0 : bi;
                 if (dist) dist[n] = b;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same scan with the reads of a whole code in flight ahead of the sums (deeper software pipeline).
+template <int R, int THREADS>
+__global__ __launch_bounds__(THREADS) void assign_scan4sd_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = (TILE_F4 + THREADS - 1) / THREADS;     // float4 per thread per tile fill (last one partial)
+    constexpr bool EVEN = TILE_F4 % THREADS == 0;
+    constexpr uint32_t PAD = TILE_BYTES;      // 256 bytes of -0.0: [PAD, PAD+128) in bank half 0, the rest in half 1
+
+    __shared__ float4 tile[TILE_F4 + 16];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const uint32_t hsel = (uint32_t)c & 1u;           // odd slots start with the upper half-row
+    const uint32_t late = ((uint32_t)c >> 1) & 1u;    // slots 2,3 of a group run one subspace behind
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
+
+    // five step offsets per code, /16, in 16-bit fields: pa = f0|f1, pb = f2|f3; the fifth fields of
+    // codes 2i and 2i+1 share pc[i]
+    static_assert(R % 2 == 0, "fifth offsets are stored two to a register");
+    uint32_t pa[R], pb[R], pc[R / 2];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        const uint32_t lo = (hsel << 2) | (uint32_t)q;                       // (hsel*64 + q*16) / 16
+        uint32_t g0 = ((pk & 255u) << 5) | (0u << 3) | lo;                   // (x*512 + m*128)/16 = x*32 + m*8
+        uint32_t g1 = (((pk >> 8) & 255u) << 5) | (1u << 3) | lo;
+        uint32_t g2 = (((pk >> 16) & 255u) << 5) | (2u << 3) | lo;
+        uint32_t g3 = ((pk >> 24) << 5) | (3u << 3) | lo;
+        uint32_t dz = (PAD >> 4) + ((late ^ 1u) ? 0u : 8u) + lo;             // early slots pad in half 0, late ones in half 1
+        uint32_t f0 = late ? dz : g0, f1 = late ? g0 : g1, f2 = late ? g1 : g2, f3 = late ? g2 : g3,
+                 f4 = late ? g3 : dz;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        if (r & 1) pc[r / 2] |= f4 << 16; else pc[r / 2] = f4;
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    // all ten reads of code r+1 (five steps, two half-rows each) are in flight while code r is summed
+    struct Set { float4 a[5], b[5]; };
+    auto issue = [&](int r) -> Set {
+        Set u;
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            uint32_t ad = (i == 0) ? sdwa_shl_word0(four, pa[r])
+                        : (i == 1) ? sdwa_shl_word1(four, pa[r])
+                        : (i == 2) ? sdwa_shl_word0(four, pb[r])
+                        : (i == 3) ? sdwa_shl_word1(four, pb[r])
+                        : (r & 1)  ? sdwa_shl_word1(four, pc[r / 2])
+                                   : sdwa_shl_word0(four, pc[r / 2]);
+            u.a[i] = lds_read16(tb, ad);
+            u.b[i] = lds_read16(tb, ad ^ 64u);
+        }
+        return u;
+    };
+    auto consume = [&](const Set& u, int r, int t) {
+        float4 sa = u.a[0], sb = u.b[0];
+#pragma unroll
+        for (int i = 1; i < 5; ++i) {
+            sa.x = sa.x + u.a[i].x; sa.y = sa.y + u.a[i].y; sa.z = sa.z + u.a[i].z; sa.w = sa.w + u.a[i].w;
+            sb.x = sb.x + u.b[i].x; sb.y = sb.y + u.b[i].y; sb.z = sb.z + u.b[i].z; sb.w = sb.w + u.b[i].w;
+        }
+        float m8 = min3_f32(sa.x, sa.y, sa.z);
+        m8 = min3_f32(m8, sa.w, sb.x);
+        m8 = min3_f32(m8, sb.y, sb.z);
+        const float nb = min3_f32(m8, sb.w, best[r]);
+        tix[r] = (nb < best[r]) ? t : tix[r];
+        best[r] = nb;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i)
+            if (EVEN || i * THREADS + tid < TILE_F4) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        // the loads of the next tile are spread over the first 5/8 of the scan
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        Set cur = issue(0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+            Set nxt = cur;
+            if (r + 1 < R) nxt = issue(r + 1);
+            consume(cur, r, t);
+            cur = nxt;
+        }
+    }
+
+    // Epilogue: as in assign_scan4x2_kernel; the four real subspace offsets are fields 0..3 (early
+    // slots) or 1..4 (late slots), and an offset is the byte position inside the tile image.
+    constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
+    static_assert(R % G == 0, "the epilogue handles codes in groups");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][8];
+        float bq[G];
+        int tq[G];
+        bool need[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint32_t a = 0, b2 = 0, c2 = 0;
+            bq[g] = INFINITY;
+            tq[g] = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; c2 = (r & 1) ? pc[r / 2] >> 16 : pc[r / 2]; tq[g] = tix[r]; bq[g] = best[r]; }
+            float smin = bq[g];
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+            need[g] = tq[g] >= 0 && bq[g] == smin;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
+            if (need[g]) {
+                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
+                const uint32_t e0 = a & 0xffffu, e1 = a >> 16, e2 = b2 & 0xffffu, e3 = b2 >> 16, e4 = c2 & 0xffffu;
+                const uint32_t o0 = ((late ? e1 : e0) << 4) & ~64u, o1 = ((late ? e2 : e1) << 4) & ~64u;
+                const uint32_t o2 = ((late ? e3 : e2) << 4) & ~64u, o3 = ((late ? e4 : e3) << 4) & ~64u;
+                w[g][0] = *reinterpret_cast<const v4f*>(gbase + o0);
+                w[g][1] = *reinterpret_cast<const v4f*>(gbase + o1);
+                w[g][2] = *reinterpret_cast<const v4f*>(gbase + o2);
+                w[g][3] = *reinterpret_cast<const v4f*>(gbase + o3);
+                w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 | 64u));
+                w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 | 64u));
+                w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 | 64u));
+                w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 | 64u));
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            v4f lo = w[g][0] + w[g][1];
+            lo = lo + w[g][2];
+            lo = lo + w[g][3];
+            v4f hi = w[g][4] + w[g][5];
+            hi = hi + w[g][6];
+            hi = hi + w[g][7];
+            if (need[g]) {
+                const int kb = tq[g] * TK + q * 4;
+                const float bb = bq[g];
+                b = bb;
+                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
+                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
+                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
+                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
+                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
+                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
+                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
+                if (lo.x == bb) { bi = kb; b = lo.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                assign[n] = (bi == IDX_NONE) ? 0 : bi;
+                if (dist) dist[n] = b;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Regrouping of M = 4 codes for the conflict-free scans below.
+//
+// A ds_read_b128 is served 16 lanes per clock, and on gfx950 those are lanes {0-3, 12-15, 20-23,
+// 24-27} and {4-7, 8-11, 16-19, 28-31} of each half-wave: with 4 lanes per code ("slot") the
+// slots {0, 3, 5, 6} and {1, 2, 4, 7} of every aligned block of 8 slots are served together
+// (measured: the bank-conflict counter reads zero only for this partition).  Such a set of four
+// codes reads conflict-free in all four subspaces when, in every subspace, the four subcodes are
+// different mod 4 -- a "residue group".
+//
+// The class of a code is its four residues as one byte (256 classes).  Take two class-valued
+// masks a, b whose 2-bit fields are non-zero and different in every subspace: the classes
+// c, c^a, c^b, c^a^b (an orbit) then differ in every subspace, so one code from each is a residue
+// group, and the residue of subspace 0 serves as the code's slot in it.  The plan goes through
+// GROUP_ROUNDS such mask pairs and takes, from every orbit, as many groups as its rarest class
+// still has; what no round can match is left over and put in groups of four as it comes.
+// Left-over groups are spread evenly between the residue groups so that every workgroup gets its
+// share of their bank conflicts.
+//
+// Three launches: per-workgroup class histograms, the plan (one workgroup), the scatter.  The
+// count and scatter kernels split the codes the same way, so the plan can hand every scatter
+// workgroup its first rank in every class and the result is deterministic.
+//
+// Nothing here affects results: the scan treats every code independently, and writes each result
+// to the code's original position.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t ORIGIN_NONE = 0xffffffffu;   // a position of the regrouped array that holds no code
+constexpr int GROUP_ROUNDS = 16;
+constexpr int GROUP_MAX_WGS = 256;              // workgroups of the count and scatter kernels
+constexpr int GROUP_THREADS = 1024;
+
+__constant__ uint8_t group_masks[GROUP_ROUNDS][2] = {
+    {0x7b, 0xae}, {0x66, 0x9b}, {0x69, 0xb7}, {0x7d, 0xaa}, {0x7b, 0x96}, {0x57, 0xbe}, {0x6f, 0xb5}, {0x77, 0x9a},
+    {0x6f, 0xb9}, {0x6d, 0xb7}, {0x5a, 0xa7}, {0x5d, 0xa6}, {0x5d, 0xaa}, {0x67, 0xb9}, {0x6d, 0x97}, {0x57, 0xae}};
+
+struct GroupPlan {
+    uint32_t first[256][GROUP_ROUNDS + 1];   // per class: rank of its first code matched in round d; [last] = all matched
+    uint32_t gbase[256][GROUP_ROUNDS];       // per class: index of the first group its orbit forms in round d
+    uint32_t lbase[256];                     // per class: index of its first left-over code among all left-overs
+    uint32_t groups, leftovers, lgroups, period_m1;   // residue groups, left-over codes, their groups of 4, D-1
+    uint32_t wg_hist[GROUP_MAX_WGS][256];    // count pass: codes per (workgroup, class); then the workgroup's first rank
+};
+
+__device__ __forceinline__ uint32_t code_class(uint32_t pk)
+{
+    return (pk & 3u) | ((pk >> 6) & 0xcu) | ((pk >> 12) & 0x30u) | ((pk >> 18) & 0xc0u);
+}
+
+// position of slot `slot` of group `u` (counting residue and left-over groups in their final order): groups
+// 2b and 2b+1 share the block of 8 slots b and take the slots the LDS serves together
+__device__ __forceinline__ int64_t group_slot_position(int64_t u, uint32_t slot)
+{
+    const uint32_t even_slots = 0x6530u, odd_slots = 0x7421u;      // {0,3,5,6} and {1,2,4,7}, 4 bits each
+    const uint32_t map = (u & 1) ? odd_slots : even_slots;
+    return (u >> 1) * 8 + ((map >> (4 * slot)) & 15u);
+}
+
+// Workgroup w of gridDim.x takes the chunks of 1024 consecutive codes w, w + gridDim.x, ...
+__global__ __launch_bounds__(GROUP_THREADS) void code_class_count_kernel(const uint8_t* __restrict__ codes, int64_t n,
+                                                                         GroupPlan* __restrict__ plan)
+{
+    __shared__ uint32_t h[256];
+    if (threadIdx.x < 256) h[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(codes);
+    for (int64_t i = (int64_t)blockIdx.x * GROUP_THREADS + threadIdx.x; i < n; i += (int64_t)gridDim.x * GROUP_THREADS)
+        atomicAdd(&h[code_class(cw[i])], 1u);
+    __syncthreads();
+    if (threadIdx.x < 256) plan->wg_hist[blockIdx.x][threadIdx.x] = h[threadIdx.x];
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        uint32_t o = __shfl_up(v, off);
+        if ((int)(threadIdx.x & 63) >= off) v += o;
+    }
+    return v;
+}
+
+// one workgroup of 1024 threads; nwg <= GROUP_MAX_WGS = workgroups of the count pass
+__global__ __launch_bounds__(1024) void code_group_plan_kernel(GroupPlan* __restrict__ plan, int nwg)
+{
+    __shared__ uint32_t part[4][256];
+    __shared__ uint32_t tot[256];
+    __shared__ uint32_t rem[256];
+    const int tid = threadIdx.x;
+    // --- class totals and every workgroup's first rank: thread (p, c) owns rows [p*rows, (p+1)*rows) of class c,
+    //     all of them loaded before the first is used
+    {
+        constexpr int ROWS_MAX = GROUP_MAX_WGS / 4;
+        const int p = tid >> 8, c = tid & 255;
+        const int rows = (nwg + 3) / 4;
+        const int w0 = p * rows;
+        // buffer addressing: one lane offset, the row as a constant offset -- no address registers per row.  Rows
+        // up to 4*rows - 1 <= 255 exist in the array; those past nwg hold nothing and are masked.
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(&plan->wg_hist[0][0], 0,
+                                                                      GROUP_MAX_WGS * 256 * 4, 0x00020000);
+        const uint32_t lane_off = (uint32_t)(w0 * 256 + c) * 4u;
+        uint32_t v[ROWS_MAX];
+#pragma unroll
+        for (int k = 0; k < ROWS_MAX; ++k) v[k] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane_off, k * 1024, 0);
+        uint32_t sum = 0;
+#pragma unroll
+        for (int k = 0; k < ROWS_MAX; ++k) {
+            if (!(k < rows && w0 + k < nwg)) v[k] = 0u;
+            sum += v[k];
+        }
+        part[p][c] = sum;
+        __syncthreads();
+        uint32_t run = 0;
+        for (int pp = 0; pp < p; ++pp) run += part[pp][c];
+#pragma unroll
+        for (int k = 0; k < ROWS_MAX; ++k) {
+            // lanes whose row is not theirs point past the end of the buffer, where stores are dropped
+            const uint32_t off = (k < rows) ? lane_off : 0x7ffffff0u;
+            __builtin_amdgcn_raw_buffer_store_b32(run, rs, off, k * 1024, 0);
+            run += v[k];
+        }
+        if (p == 0) {
+            const uint32_t t = part[0][c] + part[1][c] + part[2][c] + part[3][c];
+            tot[c] = t;
+            rem[c] = t;
+        }
+        __syncthreads();
+    }
+    if (tid >= 64) return;           // no barrier below: the matching runs in one wave
+    // --- lane j owns, in every round, the orbit led by class 4j (residue 0 in subspace 0): every class is in
+    //     exactly one orbit per round, so the lanes never touch the same entry of rem
+    //     First all rounds' group counts (a dependent chain through rem), then the prefix sums of all rounds
+    //     (independent of each other, so their cross-lane steps overlap).
+    uint32_t mm[GROUP_ROUNDS];
+#pragma unroll
+    for (int d = 0; d < GROUP_ROUNDS; ++d) {
+        const uint32_t a = group_masks[d][0], b = group_masks[d][1];
+        const uint32_t c0 = (uint32_t)tid << 2, c1 = c0 ^ a, c2 = c0 ^ b, c3 = c0 ^ a ^ b;
+        const uint32_t r0 = rem[c0], r1 = rem[c1], r2 = rem[c2], r3 = rem[c3];
+        uint32_t m = r0 < r1 ? r0 : r1;
+        m = m < r2 ? m : r2;
+        m = m < r3 ? m : r3;
+        mm[d] = m;
+        plan->first[c0][d] = tot[c0] - r0;
+        plan->first[c1][d] = tot[c1] - r1;
+        plan->first[c2][d] = tot[c2] - r2;
+        plan->first[c3][d] = tot[c3] - r3;
+        rem[c0] = r0 - m;  rem[c1] = r1 - m;  rem[c2] = r2 - m;  rem[c3] = r3 - m;
+        // one wave: its LDS accesses complete in program order, so the next round reads these values; the
+        // compiler keeps the order because the indices may alias
+        __builtin_amdgcn_wave_barrier();
+    }
+    uint32_t gtot = 0;
+#pragma unroll
+    for (int d = 0; d < GROUP_ROUNDS; ++d) {
+        const uint32_t a = group_masks[d][0], b = group_masks[d][1];
+        const uint32_t c0 = (uint32_t)tid << 2, c1 = c0 ^ a, c2 = c0 ^ b, c3 = c0 ^ a ^ b;
+        const uint32_t inc = wave_inclusive_scan(mm[d]);
+        const uint32_t base = gtot + inc - mm[d];
+        gtot += __shfl(inc, 63);
+        plan->gbase[c0][d] = base;
+        plan->gbase[c1][d] = base;
+        plan->gbase[c2][d] = base;
+        plan->gbase[c3][d] = base;
+    }
+    // --- left-overs: exclusive prefix over classes in ascending order, lane j owns classes 4j .. 4j+3
+    {
+        const uint32_t c0 = (uint32_t)tid << 2;
+        const uint32_t l0 = rem[c0], l1 = rem[c0 + 1], l2 = rem[c0 + 2], l3 = rem[c0 + 3];
+        const uint32_t mine = l0 + l1 + l2 + l3;
+        const uint32_t inc = wave_inclusive_scan(mine);
+        uint32_t e = inc - mine;
+        plan->first[c0][GROUP_ROUNDS] = tot[c0] - l0;          plan->lbase[c0] = e;      e += l0;
+        plan->first[c0 + 1][GROUP_ROUNDS] = tot[c0 + 1] - l1;  plan->lbase[c0 + 1] = e;  e += l1;
+        plan->first[c0 + 2][GROUP_ROUNDS] = tot[c0 + 2] - l2;  plan->lbase[c0 + 2] = e;  e += l2;
+        plan->first[c0 + 3][GROUP_ROUNDS] = tot[c0 + 3] - l3;  plan->lbase[c0 + 3] = e;
+        if (tid == 63) {
+            const uint32_t ltot = inc, lg = (ltot + 3u) / 4u;
+            plan->groups = gtot;
+            plan->leftovers = ltot;
+            plan->lgroups = lg;
+            plan->period_m1 = (lg > 0 && gtot >= lg) ? gtot / lg : 0u;   // D-1 residue groups between two left-over groups
+        }
+    }
+}
+
+// gco[pos] = (code, original index); positions that receive no code get (0, ORIGIN_NONE)
+__global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const uint8_t* __restrict__ codes, int64_t n,
+                                                                           const GroupPlan* __restrict__ plan,
+                                                                           uint2* __restrict__ gco, int64_t n_alloc)
+{
+    __shared__ uint32_t cur[256];
+    __shared__ uint32_t first_s[256][GROUP_ROUNDS + 1];
+    __shared__ uint32_t gbase_s[256][GROUP_ROUNDS];
+    __shared__ uint32_t lbase_s[256];
+    const int tid = threadIdx.x;
+    if (tid < 256) {
+        cur[tid] = plan->wg_hist[blockIdx.x][tid];
+        lbase_s[tid] = plan->lbase[tid];
+    }
+    for (int i = tid; i < 256 * (GROUP_ROUNDS + 1); i += GROUP_THREADS) (&first_s[0][0])[i] = (&plan->first[0][0])[i];
+    for (int i = tid; i < 256 * GROUP_ROUNDS; i += GROUP_THREADS) (&gbase_s[0][0])[i] = (&plan->gbase[0][0])[i];
+    const uint32_t gtot = plan->groups, ltot = plan->leftovers, lg = plan->lgroups, dm1 = plan->period_m1;
+    __syncthreads();
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(codes);
+    for (int64_t i = (int64_t)blockIdx.x * GROUP_THREADS + tid; i < n; i += (int64_t)gridDim.x * GROUP_THREADS) {
+        const uint32_t pk = cw[i];
+        const uint32_t c = code_class(pk);
+        const uint32_t rank = atomicAdd(&cur[c], 1u);
+        int64_t u;
+        uint32_t slot;
+        if (rank < first_s[c][GROUP_ROUNDS]) {
+            int d = 0;
+            if (rank >= first_s[c][1]) {              // most codes are matched in the first round
+#pragma unroll
+                for (int e = 1; e < GROUP_ROUNDS; ++e)
+                    if (rank >= first_s[c][e]) d = e;
+            }
+            const uint32_t g = gbase_s[c][d] + (rank - first_s[c][d]);
+            slot = c & 3u;
+            uint32_t before = dm1 ? g / dm1 : 0u;     // left-over groups placed before this group
+            if (before > lg) before = lg;
+            u = (int64_t)g + before;
+        } else {
+            const uint32_t li = lbase_s[c] + (rank - first_s[c][GROUP_ROUNDS]);
+            const uint32_t jg = li >> 2;
+            slot = li & 3u;
+            u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+        }
+        const int64_t pos = group_slot_position(u, slot);
+        if (pos < n_alloc) gco[pos] = make_uint2(pk, (uint32_t)i);
+    }
+    // holes: the unused slots of the last left-over group, the second half of the last block of 8, the tail
+    if (blockIdx.x == 0 && tid < 32) {
+        const int64_t T = (int64_t)gtot + lg;
+        int64_t pos = -1;
+        if (tid < 4) {
+            if (lg > 0 && (uint32_t)tid >= (ltot & 3u) && (ltot & 3u) != 0) {
+                const int64_t ul = dm1 ? (int64_t)(lg - 1) * (dm1 + 1) + dm1 : (int64_t)gtot + (lg - 1);
+                pos = group_slot_position(ul, (uint32_t)tid);
+            }
+        } else if (tid < 8) {
+            if (T & 1) pos = group_slot_position(T, (uint32_t)tid - 4);
+        } else {
+            pos = ((T + 1) >> 1) * 8 + (tid - 8);
+        }
+        if (pos >= 0 && pos < n_alloc) gco[pos] = make_uint2(0u, ORIGIN_NONE);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 4 scan over residue-grouped codes ("half-plane" tile image).
+//
+// Same decomposition as assign_scan4x2_kernel (4 lanes per slot, 8 centers per lane, TK = 32),
+// but the tile image is stored as eight planes, one per (subspace m, half h of the tile's
+// centers): the 64 bytes of centers 16h .. 16h+15 for subcode x sit at byte
+//      (2m + h) * 16384 + x * 64,
+// so the 64-byte bank quarter a slot reads is x mod 4 in every one of its eight reads, and both
+// halves of all four rows are reached from four per-code offsets through the instruction's
+// immediate offset: no address arithmetic beyond unpacking one 16-bit field per subspace, no
+// skew step, 3 adds per evaluation.  A 16-byte-per-lane LDS read is served 16 lanes = 4 slots per
+// clock, so it is conflict-free exactly when the four codes of a slot group have four different
+// subcodes mod 4 in that subspace.  Any order of the codes gives the same result; the order only
+// decides the speed.  The caller therefore passes the codes regrouped so that as many aligned
+// groups of four as possible have that property in all four subspaces (code_group_* kernels
+// below) as (code, original index) pairs; the result is written to the original index.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                const uint2* __restrict__ gco,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = (TILE_F4 + THREADS - 1) / THREADS;     // float4 per thread per tile fill (last one partial)
+    constexpr bool EVEN = TILE_F4 % THREADS == 0;
+    constexpr uint32_t HPLANE = 16384;      // bytes per (m, h) plane: 256 subcodes x 16 centers
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    // per code two registers of 16-bit fields: (byte offset of the lane's piece in plane (m, 0)) / 16, where the
+    // planes of m = 2, 3 are addressed from 64 KB up so that every remaining plane offset fits the DS immediate
+    uint32_t pa[R], pb[R];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = gco ? gco[n].x : *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        uint32_t f0 = ((pk & 255u) << 2) | (uint32_t)q;
+        uint32_t f1 = (((pk >> 8) & 255u) << 2) | (uint32_t)q;
+        uint32_t f2 = ((((pk >> 16) & 255u) << 2) | (uint32_t)q) + 4096u;
+        uint32_t f3 = (((pk >> 24) << 2) | (uint32_t)q) + 4096u;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    // A step is one subspace of one code: two 16-byte reads (the two halves of the tile's centers).  The
+    // reads of the next DEPTH steps are in flight while the sums of the current one are formed: with
+    // 16-byte reads the LDS pipe needs several outstanding per wave to stay busy next to the adds.
+    struct Pair { float4 a, b; };
+    auto issue = [&](int step) -> Pair {
+        const int r = step / 4, m = step % 4;
+        uint32_t ad = (m == 0) ? sdwa_shl_word0(four, pa[r])
+                    : (m == 1) ? sdwa_shl_word1(four, pa[r])
+                    : (m == 2) ? sdwa_shl_word0(four, pb[r])
+                               : sdwa_shl_word1(four, pb[r]);
+        const uint32_t po = (m & 1) ? 2 * HPLANE : 0;
+        Pair p;
+        p.a = lds_read16(tb, ad + po);
+        p.b = lds_read16(tb, ad + po + HPLANE);
+        return p;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i)
+            if (EVEN || i * THREADS + tid < TILE_F4) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        // the loads of the next tile are spread over the first 5/8 of the scan: issued in one burst they
+        // would keep every wave in the vector-memory issue queue while the LDS pipe idles
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        Pair ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+        float4 sa, sb;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+#pragma unroll
+          for (int m = 0; m < 4; ++m) {
+            const int step = 4 * r + m;
+            const Pair cur = ring[step % DEPTH];
+            if (step + DEPTH < 4 * R) ring[step % DEPTH] = issue(step + DEPTH);
+            if (m == 0) {
+                sa = cur.a;
+                sb = cur.b;
+            } else {
+                sa.x = sa.x + cur.a.x; sa.y = sa.y + cur.a.y; sa.z = sa.z + cur.a.z; sa.w = sa.w + cur.a.w;
+                sb.x = sb.x + cur.b.x; sb.y = sb.y + cur.b.y; sb.z = sb.z + cur.b.z; sb.w = sb.w + cur.b.w;
+            }
+            if (m == 3) {
+                float m8 = min3_f32(sa.x, sa.y, sa.z);
+                m8 = min3_f32(m8, sa.w, sb.x);
+                m8 = min3_f32(m8, sb.y, sb.z);
+                const float nb = min3_f32(m8, sb.w, best[r]);
+                tix[r] = (nb < best[r]) ? t : tix[r];
+                best[r] = nb;
+            }
+          }
+        }
+    }
+
+    // Epilogue: as in assign_scan4x2_kernel, on the half-plane image.
+    constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
+    static_assert(R % G == 0, "the epilogue handles codes in groups");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][8];
+        float bq[G];
+        int tq[G];
+        bool need[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint32_t a = 0, b2 = 0;
+            bq[g] = INFINITY;
+            tq[g] = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
+            float smin = bq[g];
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+            need[g] = tq[g] >= 0 && bq[g] == smin;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
+            if (need[g]) {
+                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
+                const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + 2 * HPLANE;
+                const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + 2 * HPLANE;
+                w[g][0] = *reinterpret_cast<const v4f*>(gbase + o0);
+                w[g][1] = *reinterpret_cast<const v4f*>(gbase + o1);
+                w[g][2] = *reinterpret_cast<const v4f*>(gbase + o2);
+                w[g][3] = *reinterpret_cast<const v4f*>(gbase + o3);
+                w[g][4] = *reinterpret_cast<const v4f*>(gbase + o0 + HPLANE);
+                w[g][5] = *reinterpret_cast<const v4f*>(gbase + o1 + HPLANE);
+                w[g][6] = *reinterpret_cast<const v4f*>(gbase + o2 + HPLANE);
+                w[g][7] = *reinterpret_cast<const v4f*>(gbase + o3 + HPLANE);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            v4f lo = w[g][0] + w[g][1];
+            lo = lo + w[g][2];
+            lo = lo + w[g][3];
+            v4f hi = w[g][4] + w[g][5];
+            hi = hi + w[g][6];
+            hi = hi + w[g][7];
+            if (need[g]) {
+                const int kb = tq[g] * TK + q * 4;
+                const float bb = bq[g];
+                b = bb;
+                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
+                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
+                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
+                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
+                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
+                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
+                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
+                if (lo.x == bb) { bi = kb; b = lo.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                const uint32_t og = gco ? gco[n].y : 0u;
+                const int64_t dst = gco ? (int64_t)og : n;
+                if (og != ORIGIN_NONE) {
+                    assign[dst] = (bi == IDX_NONE) ? 0 : bi;
+                    if (dist) dist[dst] = b;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 4 scan over residue-grouped codes, 16-center tiles.
+//
+// The tile is 16 centers (64 KB: img16[tile][m][x][16]), so two workgroups share a compute unit
+// and one scans while the other refills its tile between barriers.  4 lanes per slot, 4 centers
+// per lane: one 16-byte read per subspace and code at byte m*16384 + x*64 + 16q; the plane
+// offset is the instruction's immediate.  As in assign_scan4p_kernel the read is conflict-free
+// when the codes whose lanes the LDS serves together have four different subcodes mod 4, and
+// the caller passes regrouped codes with their original positions.  The reads of DEPTH codes
+// are in flight while the sums of the current one are formed.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(THREADS / 128, THREADS / 128)))
+void assign_scan4q_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                const uint2* __restrict__ gco,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 16;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int T16_F4 = TILE_F4 / 2, T16_BYTES = TILE_BYTES / 2;
+    constexpr int NF = T16_F4 / THREADS;
+    constexpr uint32_t PLANE = 16384;       // bytes per subspace plane: 256 subcodes x 16 centers
+    static_assert(T16_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+    static_assert(R % DEPTH == 0 && R >= 2 * DEPTH, "codes are consumed in rounds of DEPTH");
+
+    __shared__ float4 tile[T16_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    uint32_t pa[R], pb[R];      // 16-bit fields (x_m*64 + 16q) / 16
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t pk = gco ? gco[n].x : *reinterpret_cast<const uint32_t*>(codes + n * 4);
+        uint32_t f0 = ((pk & 255u) << 2) | (uint32_t)q;
+        uint32_t f1 = (((pk >> 8) & 255u) << 2) | (uint32_t)q;
+        uint32_t f2 = (((pk >> 16) & 255u) << 2) | (uint32_t)q;
+        uint32_t f3 = ((pk >> 24) << 2) | (uint32_t)q;
+        pa[r] = f0 | (f1 << 16);
+        pb[r] = f2 | (f3 << 16);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * T16_F4), 0, T16_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    struct Set { float4 v[4]; };
+    auto issue = [&](int r) -> Set {
+        Set u;
+        u.v[0] = lds_read16(tb, sdwa_shl_word0(four, pa[r]));
+        u.v[1] = lds_read16(tb, sdwa_shl_word1(four, pa[r]) + PLANE);
+        u.v[2] = lds_read16(tb, sdwa_shl_word0(four, pb[r]) + 2 * PLANE);
+        u.v[3] = lds_read16(tb, sdwa_shl_word1(four, pb[r]) + 3 * PLANE);
+        return u;
+    };
+    auto consume = [&](const Set& u, int r, int t) {
+        float4 s = u.v[0];
+#pragma unroll
+        for (int m = 1; m < 4; ++m) {
+            s.x = s.x + u.v[m].x; s.y = s.y + u.v[m].y; s.z = s.z + u.v[m].z; s.w = s.w + u.v[m].w;
+        }
+        const float m4 = min3_f32(s.x, s.y, s.z);
+        const float nb = min3_f32(m4, s.w, best[r]);
+        tix[r] = (nb < best[r]) ? t : tix[r];
+        best[r] = nb;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        // the loads of the next tile are spread over the first 5/8 of the scan (see assign_scan4p_kernel)
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        Set ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+#pragma unroll
+        for (int r0 = 0; r0 < R; r0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+                for (int i = 0; i < NF; ++i)
+                    if ((i * R * 5) / (NF * 8) == r0 + d) pf[i] = gload(tn, i);
+                const Set u = ring[d];
+                if (r0 + DEPTH + d < R) ring[d] = issue(r0 + DEPTH + d);
+                consume(u, r0 + d, t);
+            }
+        }
+    }
+
+    // Epilogue: recover the center inside the winning tile (re-read from the image, same bits and sum
+    // order), then merge the 4 lanes of the slot by (value, index).
+    constexpr int G = THREADS > 512 ? 2 : 4;
+    static_assert(R % G == 0, "the epilogue handles codes in groups");
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; r0 += G) {
+        v4f w[G][4];
+        float bq[G];
+        int tq[G];
+        bool need[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            uint32_t a = 0, b2 = 0;
+            bq[g] = INFINITY;
+            tq[g] = -1;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
+            float smin = bq[g];
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
+            need[g] = tq[g] >= 0 && bq[g] == smin;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
+            if (need[g]) {
+                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * T16_F4);
+                w[g][0] = *reinterpret_cast<const v4f*>(gbase + ((a & 0xffffu) << 4));
+                w[g][1] = *reinterpret_cast<const v4f*>(gbase + ((a >> 16) << 4) + PLANE);
+                w[g][2] = *reinterpret_cast<const v4f*>(gbase + ((b2 & 0xffffu) << 4) + 2 * PLANE);
+                w[g][3] = *reinterpret_cast<const v4f*>(gbase + ((b2 >> 16) << 4) + 3 * PLANE);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            v4f sv = w[g][0] + w[g][1];
+            sv = sv + w[g][2];
+            sv = sv + w[g][3];
+            if (need[g]) {
+                const int kb = tq[g] * TK + q * 4;
+                const float bb = bq[g];
+                b = bb;
+                if (sv.w == bb) { bi = kb + 3; b = sv.w; }
+                if (sv.z == bb) { bi = kb + 2; b = sv.z; }
+                if (sv.y == bb) { bi = kb + 1; b = sv.y; }
+                if (sv.x == bb) { bi = kb; b = sv.x; }
+            }
+#pragma unroll
+            for (int d = LPS / 2; d >= 1; d >>= 1) {
+                float ob = __shfl_xor(b, d);
+                int oi = __shfl_xor(bi, d);
+                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
+            }
+            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
+            if (q == 0 && n < N) {
+                const uint32_t og = gco ? gco[n].y : 0u;
+                const int64_t dst = gco ? (int64_t)og : n;
+                if (og != ORIGIN_NONE) {
+                    assign[dst] = (bi == IDX_NONE) ? 0 : bi;
+                    if (dist) dist[dst] = b;
+                }
             }
         }
     }

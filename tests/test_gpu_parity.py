@@ -88,7 +88,7 @@ def test_assign_generic_matches_oracle(env, M):
     _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=1)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31, 32, 33, 34, 35, 36, 37, 38, 39])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31, 32, 33, 34, 35, 36, 37, 38, 39, 40, 41, 42, 43, 44, 45, 46, 47, 48, 49, 50, 51, 52, 53, 54, 55, 56, 57, 60, 61, 62, 63, 64, 65])
 def test_assign_every_compiled_shape(env, variant):
     w = workload(1, N=9001, K=131, T=40)
     W = env["W"]
@@ -96,6 +96,40 @@ def test_assign_every_compiled_shape(env, variant):
     centers = codes[W.init_center_indices(w)].copy()
     tables = env["oracle"].build_tables(W.codewords(w))
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+
+
+@pytest.mark.parametrize("variant", [70, 71, 72, 73, 74])
+@pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 200003), ("uniform", 4093), ("uniform", 7),
+                                    ("uniform", 1), ("one_class", 5000), ("two_classes", 6001), ("latin", 8192)])
+def test_assign_regrouped_scan(env, variant, kind, N):
+    """M = 4 scan over regrouped codes: the regrouping (residue groups, left-overs, holes) must not change
+    any result.  Class mixes: typical, all codes in one residue class (everything left over), two classes,
+    and perfectly balanced classes (no left-overs)."""
+    W = env["W"]
+    rng = np.random.default_rng(N + variant)
+    w = workload(1, N=max(N, 200), K=131, T=40)
+    allc = W.codes_numpy(w)
+    centers = allc[W.init_center_indices(w)].copy()
+    if kind == "templates":
+        codes = allc[:N]
+    else:
+        codes = rng.integers(0, 256, size=(N, 4), dtype=np.uint8)
+        if kind == "one_class":
+            codes &= 0xFC
+        elif kind == "two_classes":
+            codes = (codes & 0xFC) | (rng.integers(0, 2, size=(N, 1), dtype=np.uint8) * 3)
+        elif kind == "latin":
+            lat = np.stack([rng.permuted(np.tile(np.arange(4, dtype=np.uint8), (N // 4, 1)), axis=1)
+                            for _ in range(4)], axis=2).reshape(-1, 4)
+            codes = (codes & 0xFC) | lat
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+    if variant == 70:
+        ham = np.ones((4, 256, 256), np.float32)
+        for m in range(4):
+            np.fill_diagonal(ham[m], 0)
+        small = (codes % 3).astype(np.uint8)
+        _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
 
 
 @pytest.mark.parametrize("M,variant", [(8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (16, 1), (16, 2), (16, 3), (16, 4),
