@@ -35,7 +35,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, gco_off, plan_off, total;
+        gid_bytes, gco_off, plan_off, rows_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -86,8 +86,10 @@ Carve carve(int64_t N, int M, int K)
     c.gid_off = off;
     c.gid_bytes = (hp.KT >= 1 && hp.groups <= 255) ? (size_t)N : 0;
     off += align256(c.gid_bytes);
-    c.gco_off = c.plan_off = off;
+    c.gco_off = c.plan_off = c.rows_off = off;
     if (M == 4) {
+        c.rows_off = off;                    // second copy of the tile images, read by the half-plane scan's epilogue
+        off += align256(c.img_bytes);
         const int64_t na = group_alloc(N < GROUP_CHUNK_MAX ? N : GROUP_CHUNK_MAX);
         c.gco_off = off;
         off += align256((size_t)na * sizeof(uint2));
@@ -168,13 +170,13 @@ void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntile
 }
 
 template <int R, int THREADS, int DEPTH>
-void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, int ntiles,
-                   int32_t* assign, float* dist, hipStream_t st)
+void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, const float4* rows,
+                   int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     constexpr int C = (THREADS / 4) * R;
     int64_t nwg = (N + C - 1) / C;
     hipLaunchKernelGGL((assign_scan4p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, gco,
-                       img, ntiles, assign, dist);
+                       img, rows, ntiles, assign, dist);
 }
 
 template <int R, int THREADS, int DEPTH>
@@ -221,19 +223,19 @@ inline int variant_layout(int M, int variant)
 }
 
 template <int M>
-void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
-                   float* dist, hipStream_t st);
+void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows, int ntiles,
+                   int32_t* assign, float* dist, hipStream_t st);
 
 // M = 4 scans over regrouped codes: variants 70..79
-void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
-                         float* dist, hipStream_t st)
+void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
+                         int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     switch (variant) {
-        case 71: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
-        case 72: launch_scan4p<24, 512, 4>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
-        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
-        case 74: launch_scan4p<32, 512, 2>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;
-        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, ntiles, assign, dist, st); break;   // 70
+        case 71: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 72: launch_scan4p<24, 512, 4>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 74: launch_scan4p<32, 512, 2>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;   // 70
     }
 }
 
@@ -252,8 +254,8 @@ pqkm_status regroup_codes(const uint8_t* codes, int64_t cnt, uint2* gco, GroupPl
 }
 
 template <>
-void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
-                      float* dist, hipStream_t st)
+void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows,
+                      int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     switch (variant) {
         case 1: launch_scan<4, 16, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
@@ -294,16 +296,16 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 37: launch_scan4s<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 38: launch_scan4s<20, 768>(codes, N, img, ntiles, assign, dist, st); break;
         case 39: launch_scan4s<14, 1024>(codes, N, img, ntiles, assign, dist, st); break;
-        case 40: launch_scan4p<16, 1024, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 41: launch_scan4p<16, 1024, 1>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 42: launch_scan4p<8, 1024, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 43: launch_scan4p<16, 768, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 44: launch_scan4p<24, 512, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 45: launch_scan4p<32, 512, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 46: launch_scan4p<28, 512, 3>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 47: launch_scan4p<20, 768, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 48: launch_scan4p<32, 512, 3>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
-        case 49: launch_scan4p<24, 512, 6>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 40: launch_scan4p<16, 1024, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 41: launch_scan4p<16, 1024, 1>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 42: launch_scan4p<8, 1024, 4>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 43: launch_scan4p<16, 768, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 44: launch_scan4p<24, 512, 4>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 45: launch_scan4p<32, 512, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 46: launch_scan4p<28, 512, 3>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 47: launch_scan4p<20, 768, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 48: launch_scan4p<32, 512, 3>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
+        case 49: launch_scan4p<24, 512, 6>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 50: launch_scan4q<32, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
         case 51: launch_scan4q<16, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
         case 52: launch_scan4q<12, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
@@ -322,8 +324,8 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
     }
 }
 template <>
-void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
-                      float* dist, hipStream_t st)
+void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows,
+                      int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     switch (variant) {
         case 1: launch_scan<8, 8, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
@@ -335,8 +337,8 @@ void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4
     }
 }
 template <>
-void launch_scan_M<16>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
-                       float* dist, hipStream_t st)
+void launch_scan_M<16>(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows,
+                       int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     switch (variant) {
         case 1: launch_scan<16, 4, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
@@ -347,8 +349,8 @@ void launch_scan_M<16>(int variant, const uint8_t* codes, int64_t N, const float
     }
 }
 template <>
-void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign,
-                       float* dist, hipStream_t st)
+void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows,
+                       int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
     switch (variant) {
         case 1: launch_scan<32, 2, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
@@ -364,10 +366,12 @@ void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float
 // to pay for regrouping (a pass over the codes) and the subspace-skewed scan otherwise.
 inline int effective_variant(int M, int variant, int64_t N, int K)
 {
+    // the half-plane scans address the tile images through one 32-bit buffer offset: below 4 GB of images only
+    const bool img32 = (int64_t)((K + 31) / 32) * TILE_BYTES < (int64_t)0xfff00000;
+    if (M == 4 && !img32 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 34;
     if (M != 4 || variant != 0) return variant;
-    if (K < 128 || N < 65536) return 34;
-    const int64_t wgs28 = (N + 128 * 28 - 1) / (128 * 28);
-    return wgs28 > 2048 ? 71 : 70;       // many rounds of workgroups: 28 codes per lane-slot (no spill); else 32
+    if (K < 128 || N < 65536 || !img32) return 34;
+    return 70;                            // 32 codes per lane-slot, 512 threads: the fastest measured shape at every size
 }
 inline bool variant_grouped(int M, int variant) { return M == 4 && variant >= 70 && variant <= 79; }
 
@@ -386,7 +390,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
                            centers, K, tables, img, total);
     else if (layout == 2 && M == 4)
         hipLaunchKernelGGL((tile_image_kernel<4, 2>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           centers, K, tables, img, total);
+                           centers, K, tables, img, total, reinterpret_cast<float*>(ws + c.rows_off));
     else if (layout == 1)
         hipLaunchKernelGGL((tile_image_kernel<M, 1>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            centers, K, tables, img, total);
@@ -397,6 +401,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     const bool grouped = variant_grouped(M, variant);
     int64_t per_launch = opt.launch_codes;
     if (grouped && per_launch > GROUP_CHUNK_MAX) per_launch = GROUP_CHUNK_MAX;
+    const float4* rows = reinterpret_cast<const float4*>(ws + c.rows_off);
     uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
     for (int64_t n0 = 0; n0 < N; n0 += per_launch) {
@@ -420,10 +425,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         }
         if (prof) hipEventRecord(ev.a, st);
         if (grouped)
-            launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
-                                assign + n0, dist ? dist + n0 : nullptr, st);
+            launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows,
+                                (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st);
         else
-            launch_scan_M<M>(variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), (int)ntiles,
+            launch_scan_M<M>(variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                              assign + n0, dist ? dist + n0 : nullptr, st);
         if (prof) hipEventRecord(ev.b, st);
         if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;

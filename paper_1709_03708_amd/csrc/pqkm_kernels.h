@@ -84,11 +84,12 @@ __global__ __launch_bounds__(256) void assign_generic_kernel(const uint8_t* __re
 // LAYOUT 1 is the alternative order img[tile][x][m][kin] used by the subspace-skewed scan, in which
 // the LDS bank half of a row is decided by the parity of m instead of the parity of x.  LAYOUT 2
 // (M = 4, TK = 32 only) is img[tile][m][h][x][kin % 16] with h = kin / 16: eight planes of 16 KB.
+// With LAYOUT 2 the kernel can also write a second copy of the images in the order of LAYOUT 0.
 // TK defaults to the 128 KB tile; the 16-center scan for M = 4 uses LAYOUT 0 with TK = 16 (64 KB tiles).
 template <int M, int LAYOUT = 0, int TK = 128 / M>
 __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restrict__ centers, int K,
                                                          const float* __restrict__ tables, float* __restrict__ img,
-                                                         int64_t total)
+                                                         int64_t total, float* __restrict__ rows = nullptr)
 {
     int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= total) return;
@@ -111,6 +112,9 @@ __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restri
     float v = INFINITY;
     if (k < K) v = tables[((size_t)m * L + x) * L + centers[k * M + m]];
     img[e] = v;
+    // second copy in the plain order [tile][m][x][k] (LAYOUT 2 only): one 128-byte line per (tile, m, x), read by
+    // the epilogue of the half-plane scan
+    if (LAYOUT == 2 && rows) rows[((tile * M + m) * L + x) * TK + kin] = v;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1288,22 +1292,27 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
             if (before > lg) before = lg;
             u = (int64_t)g + before;
         } else {
+            // left-overs come sorted by class: group j takes the left-overs j, j + lg, j + 2 lg, j + 3 lg, four
+            // different stretches of that order, rather than four neighbours of (mostly) one class
             const uint32_t li = lbase_s[c] + (rank - first_s[c][GROUP_ROUNDS]);
-            const uint32_t jg = li >> 2;
-            slot = li & 3u;
+            const uint32_t jg = li % lg;
+            slot = li / lg;
             u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
         }
         const int64_t pos = group_slot_position(u, slot);
         if (pos < n_alloc) gco[pos] = make_uint2(pk, (uint32_t)i);
     }
-    // holes: the unused slots of the last left-over group, the second half of the last block of 8, the tail
+    // holes: the empty places of the left-over groups, the second half of the last block of 8, the tail
     if (blockIdx.x == 0 && tid < 32) {
         const int64_t T = (int64_t)gtot + lg;
         int64_t pos = -1;
         if (tid < 4) {
-            if (lg > 0 && (uint32_t)tid >= (ltot & 3u) && (ltot & 3u) != 0) {
-                const int64_t ul = dm1 ? (int64_t)(lg - 1) * (dm1 + 1) + dm1 : (int64_t)gtot + (lg - 1);
-                pos = group_slot_position(ul, (uint32_t)tid);
+            // the left-over groups have 4 lg >= ltot places: the places ltot .. 4 lg - 1 (at most 3) stay empty
+            const uint32_t li = ltot + (uint32_t)tid;
+            if (li < 4u * lg) {
+                const uint32_t jg = li % lg;
+                const int64_t ul = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+                pos = group_slot_position(ul, li / lg);
             }
         } else if (tid < 8) {
             if (T & 1) pos = group_slot_position(T, (uint32_t)tid - 4);
@@ -1334,7 +1343,8 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
 template <int R, int THREADS, int DEPTH>
 __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* __restrict__ codes, int64_t N,
                                                                 const uint2* __restrict__ gco,
-                                                                const float4* __restrict__ img, int ntiles,
+                                                                const float4* __restrict__ img,
+                                                                const float4* __restrict__ rows, int ntiles,
                                                                 int32_t* __restrict__ assign,
                                                                 float* __restrict__ dist)
 {
@@ -1444,80 +1454,135 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
         }
     }
 
-    // Epilogue: as in assign_scan4x2_kernel, on the half-plane image.
-    constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
-    static_assert(R % G == 0, "the epilogue handles codes in groups");
+    // Epilogue: recover the center inside the winning tile.  During the scan four lanes share a code; here the
+    // work is transposed through LDS so that every lane finishes codes of its own (R/4 of them) instead of four
+    // lanes walking through the same R codes: each lane leaves (minimum, tile) per code in LDS, then lane l takes
+    // the codes l, l + THREADS, ...: the slot minimum is the smallest of the four minima, the winning tile the
+    // lowest tile among the lanes that attain it (a lower tile means lower center indices), and for every lane
+    // position q that attains it in that tile the 8 sums of its centers are rebuilt from the tile image in global
+    // memory (same bits, same sum order) and the lowest center index with that sum is kept.  Almost always there
+    // is one such q; the loop over them only repeats on exact ties between lane positions.
+    static_assert(R % 4 == 0 && R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+    constexpr int CPL = R / 4;                      // codes per lane in the epilogue
+    constexpr int EB = THREADS > 768 ? 2 : 4;       // codes whose image reads are in flight together
+    __syncthreads();                                // every wave is done with the last tile
+    {
+        float2* rec = reinterpret_cast<float2*>(tile);
+#pragma unroll
+        for (int r = 0; r < R; ++r)                  // record index = 4 * (code index in the workgroup) + q
+            rec[(r * SLOTS + c) * 4 + q] = make_float2(best[r], __builtin_bit_cast(float, tix[r]));
+    }
+    __syncthreads();
+    // The reads go to the copy of the images in the order [tile][m][x][32 centers]: the 8 pieces of a code are
+    // then in 4 cache lines instead of 8 (a scattered 16-byte read moves a whole 128-byte line, and this traffic
+    // is what the epilogue costs).  The whole copy sits behind one buffer descriptor (the host uses this kernel
+    // only while it is below 4 GB): a 32-bit lane offset per subspace, the subspace plane as a scalar offset;
+    // offsets past the end return zero.
+    __amdgpu_buffer_rsrc_t rs_img = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(rows), 0, (uint32_t)ntiles * (uint32_t)TILE_BYTES, 0x00020000);
+    constexpr int TNONE = 0x7fffffff;
 #pragma unroll 1
-    for (int r0 = 0; r0 < R; r0 += G) {
-        v4f w[G][8];
-        float bq[G];
-        int tq[G];
-        bool need[G];
+    for (int i0 = 0; i0 < CPL; i0 += EB) {
+        float smin[EB];
+        int tmin[EB], bi[EB];
+        uint32_t cand[EB], pk[EB], og[EB];
+        v4f w[EB][8];
+        int qq[EB];
+        // phase A: records, code, original position
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint32_t a = 0, b2 = 0;
-            bq[g] = INFINITY;
-            tq[g] = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
-            float smin = bq[g];
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
-            need[g] = tq[g] >= 0 && bq[g] == smin;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
-            if (need[g]) {
-                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
-                const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + 2 * HPLANE;
-                const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + 2 * HPLANE;
-                w[g][0] = *reinterpret_cast<const v4f*>(gbase + o0);
-                w[g][1] = *reinterpret_cast<const v4f*>(gbase + o1);
-                w[g][2] = *reinterpret_cast<const v4f*>(gbase + o2);
-                w[g][3] = *reinterpret_cast<const v4f*>(gbase + o3);
-                w[g][4] = *reinterpret_cast<const v4f*>(gbase + o0 + HPLANE);
-                w[g][5] = *reinterpret_cast<const v4f*>(gbase + o1 + HPLANE);
-                w[g][6] = *reinterpret_cast<const v4f*>(gbase + o2 + HPLANE);
-                w[g][7] = *reinterpret_cast<const v4f*>(gbase + o3 + HPLANE);
+        for (int e = 0; e < EB; ++e) {
+            if (i0 + e >= CPL) { cand[e] = 0u; og[e] = ORIGIN_NONE; pk[e] = 0u; smin[e] = 0.f; tmin[e] = 0; bi[e] = IDX_NONE; continue; }
+            const int j = (i0 + e) * THREADS + tid;
+            int64_t n = base + j;
+            const bool live = n < N;
+            if (!live) n = N - 1;
+            const float4 ra = lds_read16(tb, (uint32_t)j * 32u), rb = lds_read16(tb, (uint32_t)j * 32u + 16u);
+            const float b0 = ra.x, b1 = ra.z, b2 = rb.x, b3 = rb.z;
+            const int t0 = __builtin_bit_cast(int, ra.y), t1 = __builtin_bit_cast(int, ra.w);
+            const int t2 = __builtin_bit_cast(int, rb.y), t3 = __builtin_bit_cast(int, rb.w);
+            const float sm = __builtin_fminf(__builtin_fminf(b0, b1), __builtin_fminf(b2, b3));
+            const int c0 = (b0 == sm && t0 >= 0) ? t0 : TNONE, c1 = (b1 == sm && t1 >= 0) ? t1 : TNONE;
+            const int c2 = (b2 == sm && t2 >= 0) ? t2 : TNONE, c3 = (b3 == sm && t3 >= 0) ? t3 : TNONE;
+            int tm = c0 < c1 ? c0 : c1;
+            tm = tm < c2 ? tm : c2;
+            tm = tm < c3 ? tm : c3;
+            uint32_t cd = (uint32_t)(c0 == tm) | ((uint32_t)(c1 == tm) << 1) | ((uint32_t)(c2 == tm) << 2) |
+                          ((uint32_t)(c3 == tm) << 3);
+            if (tm == TNONE || !live) cd = 0u;
+            smin[e] = sm;
+            tmin[e] = tm;
+            cand[e] = cd;
+            bi[e] = IDX_NONE;
+            if (gco) {
+                const uint2 g = gco[n];
+                pk[e] = g.x;
+                og[e] = live ? g.y : ORIGIN_NONE;
+            } else {
+                pk[e] = *reinterpret_cast<const uint32_t*>(codes + n * 4);
+                og[e] = live ? 0u : ORIGIN_NONE;
             }
         }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float b = INFINITY;
-            int bi = IDX_NONE;
-            v4f lo = w[g][0] + w[g][1];
-            lo = lo + w[g][2];
-            lo = lo + w[g][3];
-            v4f hi = w[g][4] + w[g][5];
-            hi = hi + w[g][6];
-            hi = hi + w[g][7];
-            if (need[g]) {
-                const int kb = tq[g] * TK + q * 4;
-                const float bb = bq[g];
-                b = bb;
-                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
-                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
-                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
-                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
-                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
-                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
-                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
-                if (lo.x == bb) { bi = kb; b = lo.x; }
+        // phase B: lowest candidate position of every code, all reads in flight together; then any further
+        // candidates (exact ties between lane positions), one at a time
+        auto ep_issue = [&](int e) {
+            const uint32_t cd = cand[e];
+            const int qe = cd ? (int)__builtin_ctz(cd) : 0;
+            qq[e] = qe;
+            const uint32_t tb0 = cd ? (uint32_t)tmin[e] * (uint32_t)TILE_BYTES + (uint32_t)qe * 16u : 0xfff00000u;
+            const uint32_t o0 = tb0 + ((pk[e] & 255u) << 7), o1 = tb0 + (((pk[e] >> 8) & 255u) << 7);
+            const uint32_t o2 = tb0 + (((pk[e] >> 16) & 255u) << 7), o3 = tb0 + ((pk[e] >> 24) << 7);
+            constexpr int MP = 32768;             // bytes per subspace in a tile of the row copy
+            w[e][0] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o0, 0, 0));
+            w[e][4] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o0, 64, 0));
+            w[e][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o1, MP, 0));
+            w[e][5] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o1, MP + 64, 0));
+            w[e][2] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o2, 2 * MP, 0));
+            w[e][6] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o2, 2 * MP + 64, 0));
+            w[e][3] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o3, 3 * MP, 0));
+            w[e][7] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o3, 3 * MP + 64, 0));
+        };
+        auto ep_finish = [&](int e) {
+            if (cand[e]) {
+                v4f lo = w[e][0] + w[e][1];
+                lo = lo + w[e][2];
+                lo = lo + w[e][3];
+                v4f hi = w[e][4] + w[e][5];
+                hi = hi + w[e][6];
+                hi = hi + w[e][7];
+                const int kb = tmin[e] * TK + qq[e] * 4;
+                const float bb = smin[e];
+                int k = IDX_NONE;
+                if (hi.w == bb) k = kb + 19;
+                if (hi.z == bb) k = kb + 18;
+                if (hi.y == bb) k = kb + 17;
+                if (hi.x == bb) k = kb + 16;
+                if (lo.w == bb) k = kb + 3;
+                if (lo.z == bb) k = kb + 2;
+                if (lo.y == bb) k = kb + 1;
+                if (lo.x == bb) k = kb;
+                bi[e] = k < bi[e] ? k : bi[e];
+                cand[e] &= cand[e] - 1u;
             }
+        };
+        // one trip handles the lowest candidate position of every code of the batch; further trips only happen
+        // on exact ties between lane positions (the loop is one copy of the code: this part of the kernel runs
+        // once per workgroup, from a cold instruction cache, and its size is its cost)
+        bool more;
+        do {
 #pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
-                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-            }
-            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
-            if (q == 0 && n < N) {
-                const uint32_t og = gco ? gco[n].y : 0u;
-                const int64_t dst = gco ? (int64_t)og : n;
-                if (og != ORIGIN_NONE) {
-                    assign[dst] = (bi == IDX_NONE) ? 0 : bi;
-                    if (dist) dist[dst] = b;
-                }
+            for (int e = 0; e < EB; ++e) ep_issue(e);
+#pragma unroll
+            for (int e = 0; e < EB; ++e) ep_finish(e);
+            more = false;
+#pragma unroll
+            for (int e = 0; e < EB; ++e) more = more || cand[e] != 0u;
+        } while (__any(more));
+#pragma unroll
+        for (int e = 0; e < EB; ++e) {
+            if (og[e] != ORIGIN_NONE) {
+                const int64_t dst = gco ? (int64_t)og[e] : base + (i0 + e) * THREADS + tid;
+                assign[dst] = (bi[e] == IDX_NONE) ? 0 : bi[e];
+                if (dist) dist[dst] = smin[e];
             }
         }
     }
