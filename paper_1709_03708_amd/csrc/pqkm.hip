@@ -139,26 +139,6 @@ void launch_scan(const uint8_t* codes, int64_t N, const float4* img, int ntiles,
                        img, ntiles, assign, dist);
 }
 
-template <int R, int THREADS, bool PF>
-void launch_scan4(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
-                  hipStream_t st)
-{
-    constexpr int C = (THREADS / 8) * R;
-    int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan4_kernel<R, THREADS, PF>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, img,
-                       ntiles, assign, dist);
-}
-
-template <int R, int THREADS, bool PF>
-void launch_scan4x2(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
-                    hipStream_t st)
-{
-    constexpr int C = (THREADS / 4) * R;
-    int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan4x2_kernel<R, THREADS, PF>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
-                       img, ntiles, assign, dist);
-}
-
 template <int R, int THREADS>
 void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
                    hipStream_t st)
@@ -179,34 +159,14 @@ void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const floa
                        img, rows, ntiles, assign, dist);
 }
 
-template <int R, int THREADS, int DEPTH>
-void launch_scan4q(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, int ntiles,
-                   int32_t* assign, float* dist, hipStream_t st)
-{
-    constexpr int C = (THREADS / 4) * R;
-    int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan4q_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
-                       gco, img, ntiles, assign, dist);
-}
-
-template <int R, int THREADS>
-void launch_scan4sd(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
-                    hipStream_t st)
-{
-    constexpr int C = (THREADS / 4) * R;
-    int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan4sd_kernel<R, THREADS>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, img,
-                       ntiles, assign, dist);
-}
-
-template <int M, int R, int THREADS>
+template <int M, int R, int THREADS, int DEPTH = 1>
 void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int ntiles, int32_t* assign, float* dist,
                       hipStream_t st)
 {
     constexpr int C = (THREADS / (128 / M / 4)) * R;
     int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan_skew_kernel<M, R, THREADS>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
-                       img, ntiles, assign, dist);
+    hipLaunchKernelGGL((assign_scan_skew_kernel<M, R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes,
+                       N, img, ntiles, assign, dist);
 }
 
 // tile image layout a scan shape reads: 0 = [m][x][k], 1 = [x][m][k] (subspace-skewed scans), 2 = half planes
@@ -216,8 +176,7 @@ inline int variant_layout(int M, int variant)
 {
     if (M == 4) {
         if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79)) return 2;
-        if (variant >= 50 && variant <= 59) return 3;     // [m][x][k] with 16-center tiles
-        return (variant == 0 || (variant >= 30 && variant <= 39) || (variant >= 60 && variant <= 69)) ? 1 : 0;
+        return (variant >= 30 && variant <= 39) ? 1 : 0;
     }
     return variant != 1 ? 1 : 0;  // M = 8, 16, 32: every shape but 1 (the unskewed tiled scan) is skewed
 }
@@ -232,9 +191,7 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
 {
     switch (variant) {
         case 71: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 72: launch_scan4p<24, 512, 4>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
         case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 74: launch_scan4p<32, 512, 2>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
         default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;   // 70
     }
 }
@@ -259,67 +216,16 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
 {
     switch (variant) {
         case 1: launch_scan<4, 16, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 2: launch_scan<4, 32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
         case 3: launch_scan<4, 16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 4: launch_scan<4, 24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
         case 5: launch_scan<4, 8, 1024, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 6: launch_scan<4, 12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 7: launch_scan<4, 32, 256, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 8: launch_scan<4, 32, 256, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 10: launch_scan4<32, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 11: launch_scan4<32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 12: launch_scan4<24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 13: launch_scan4<16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 14: launch_scan4<16, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 15: launch_scan4<16, 1024, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 16: launch_scan4<28, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 17: launch_scan4<20, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 18: launch_scan4<8, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 19: launch_scan4<12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 20: launch_scan4x2<32, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 21: launch_scan4x2<24, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 22: launch_scan4x2<16, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 23: launch_scan4x2<12, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 24: launch_scan4x2<8, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 25: launch_scan4x2<16, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 26: launch_scan4x2<32, 512, false>(codes, N, img, ntiles, assign, dist, st); break;
-        case 27: launch_scan4x2<28, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 28: launch_scan4x2<14, 1024, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 29: launch_scan4x2<20, 512, true>(codes, N, img, ntiles, assign, dist, st); break;
-        case 30: launch_scan4s<24, 512>(codes, N, img, ntiles, assign, dist, st); break;
-        case 31: launch_scan4s<24, 768>(codes, N, img, ntiles, assign, dist, st); break;
         case 32: launch_scan4s<16, 768>(codes, N, img, ntiles, assign, dist, st); break;
-        case 33: launch_scan4s<12, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 34: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
-        case 35: launch_scan4s<20, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 36: launch_scan4s<16, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 37: launch_scan4s<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
-        case 38: launch_scan4s<20, 768>(codes, N, img, ntiles, assign, dist, st); break;
-        case 39: launch_scan4s<14, 1024>(codes, N, img, ntiles, assign, dist, st); break;
-        case 40: launch_scan4p<16, 1024, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 41: launch_scan4p<16, 1024, 1>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 42: launch_scan4p<8, 1024, 4>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 43: launch_scan4p<16, 768, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 44: launch_scan4p<24, 512, 4>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 45: launch_scan4p<32, 512, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 46: launch_scan4p<28, 512, 3>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 47: launch_scan4p<20, 768, 2>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 48: launch_scan4p<32, 512, 3>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 49: launch_scan4p<24, 512, 6>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
-        case 50: launch_scan4q<32, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 51: launch_scan4q<16, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 52: launch_scan4q<12, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 53: launch_scan4q<32, 256, 4>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 54: launch_scan4q<48, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 55: launch_scan4q<32, 512, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 56: launch_scan4q<16, 512, 4>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 57: launch_scan4q<16, 256, 2>(codes, N, nullptr, img, 2 * ntiles, assign, dist, st); break;
-        case 60: launch_scan4sd<16, 512>(codes, N, img, ntiles, assign, dist, st); break;
-        case 61: launch_scan4sd<20, 512>(codes, N, img, ntiles, assign, dist, st); break;
-        case 62: launch_scan4sd<24, 512>(codes, N, img, ntiles, assign, dist, st); break;
-        case 63: launch_scan4sd<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
-        case 64: launch_scan4sd<12, 768>(codes, N, img, ntiles, assign, dist, st); break;
-        case 65: launch_scan4sd<16, 768>(codes, N, img, ntiles, assign, dist, st); break;
         default: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
@@ -385,10 +291,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
     const int variant = effective_variant(M, opt.scan_variant, N, K);
     const int layout = variant_layout(M, variant);
-    if (layout == 3 && M == 4)
-        hipLaunchKernelGGL((tile_image_kernel<4, 0, 16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           centers, K, tables, img, total);
-    else if (layout == 2 && M == 4)
+    if (layout == 2 && M == 4)
         hipLaunchKernelGGL((tile_image_kernel<4, 2>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            centers, K, tables, img, total, reinterpret_cast<float*>(ws + c.rows_off));
     else if (layout == 1)

@@ -85,7 +85,6 @@ __global__ __launch_bounds__(256) void assign_generic_kernel(const uint8_t* __re
 // the LDS bank half of a row is decided by the parity of m instead of the parity of x.  LAYOUT 2
 // (M = 4, TK = 32 only) is img[tile][m][h][x][kin % 16] with h = kin / 16: eight planes of 16 KB.
 // With LAYOUT 2 the kernel can also write a second copy of the images in the order of LAYOUT 0.
-// TK defaults to the 128 KB tile; the 16-center scan for M = 4 uses LAYOUT 0 with TK = 16 (64 KB tiles).
 template <int M, int LAYOUT = 0, int TK = 128 / M>
 __global__ __launch_bounds__(256) void tile_image_kernel(const uint8_t* __restrict__ centers, int K,
                                                          const float* __restrict__ tables, float* __restrict__ img,
@@ -267,19 +266,17 @@ __global__ __launch_bounds__(THREADS) void assign_scan_kernel(const uint8_t* __r
 }
 
 // ---------------------------------------------------------------------------------------------
-// M = 4 specialisation of the LDS-tiled scan (32/64-bit SIFT-like codes are the paper's main
-// workload, Tab. 3 and Tab. 5).  Same decomposition as above (TK = 32 centers per tile, 8 lanes
-// per slot, one ds_read_b128 per lane, code and subspace), tuned for the register file:
+// Helpers of the M = 4 scans (32-bit SIFT-like codes are the paper's main workload, Tab. 3 and
+// Tab. 5).  These kernels are tuned for the register file:
 //
-//  * per code and lane only 4 registers persist: two words of packed, pre-scaled LDS row
-//    offsets (four 16-bit fields (x_m*128 + 16q)/16, the two upper subspaces biased by 64 KB so
-//    that the remaining plane offset fits the 16-bit DS immediate; one SDWA shift unpacks a
-//    field), the running minimum and the index of the TILE in which it last improved;
-//  * the minimum is tracked with two v_min3 per 4 centers and one compare; which of the lane's
-//    4 centers of that tile attains it is recovered once, after the last tile, by re-reading
-//    those 4x4 entries from the tile image in global memory (same bits, same sum order) and
+//  * per code and lane only a few registers persist: words of packed, pre-scaled LDS row offsets
+//    (16-bit fields, byte offset / 16; one SDWA shift unpacks a field), the running minimum and
+//    the index of the TILE in which it last improved;
+//  * the minimum over the lane's centers of a tile is tracked with v_min3 and one compare; which
+//    center of that tile attains it is recovered once, after the last tile, by re-reading the
+//    terms of those sums from the tile image in global memory (same bits, same sum order) and
 //    taking the first equal one -- the same center a sequential strict "<" scan would keep;
-//  * LDS reads of code r+1 are issued before the sums of code r are formed;
+//  * LDS reads run ahead of the sums that consume them;
 //  * the next tile is prefetched from global memory into registers while the current one is
 //    being scanned, so only the LDS write of the fill is exposed between two barriers.
 // ---------------------------------------------------------------------------------------------
@@ -299,373 +296,15 @@ __device__ __forceinline__ uint32_t sdwa_shl_word1(uint32_t sh, uint32_t v)
 }
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-struct Quad4 { float4 v0, v1, v2, v3; };
-
-template <int R, int THREADS, bool PREFETCH>
-__global__ __launch_bounds__(THREADS) void assign_scan4_kernel(const uint8_t* __restrict__ codes, int64_t N,
-                                                               const float4* __restrict__ img, int ntiles,
-                                                               int32_t* __restrict__ assign,
-                                                               float* __restrict__ dist)
-{
-    constexpr int LPS = 8, TK = 32;
-    constexpr int SLOTS = THREADS / LPS;
-    constexpr int C = SLOTS * R;
-    constexpr int NF = TILE_F4 / THREADS;
-    constexpr int PLANE = 32768;            // bytes per subspace plane: 256 rows of 128 bytes
-    static_assert(R % 2 == 0, "the read pipeline handles codes in pairs");
-
-    __shared__ float4 tile[TILE_F4];
-    const char* tb = reinterpret_cast<const char*>(tile);
-
-    const int tid = threadIdx.x;
-    const int q = tid % LPS;
-    const int c = tid / LPS;
-    const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
-
-    uint32_t pa[R], pb[R];
-    float best[R];
-    int tix[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        int64_t n = base + (int64_t)r * SLOTS + c;
-        if (n >= N) n = N - 1;
-        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
-        uint32_t f0 = ((pk & 255u) << 3) | q;
-        uint32_t f1 = (((pk >> 8) & 255u) << 3) | q;
-        uint32_t f2 = ((((pk >> 16) & 255u) << 3) | q) + 4096u;
-        uint32_t f3 = (((pk >> 24) << 3) | q) + 4096u;
-        pa[r] = f0 | (f1 << 16);
-        pb[r] = f2 | (f3 << 16);
-        best[r] = INFINITY;
-        tix[r] = -1;
-    }
-
-    // tile fill addressing: one buffer descriptor per tile (wave-uniform, in SGPRs), a scalar
-    // offset per 16-byte-per-thread slab and a single 32-bit lane offset
-    const uint32_t lane_off = (uint32_t)tid * 16u;
-    v4f* ltile = reinterpret_cast<v4f*>(tile);
-    auto gload = [&](int t, int i) -> v4f {
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
-        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
-    };
-    v4f pf[NF];
-    if (PREFETCH) {
-#pragma unroll
-        for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
-    }
-
-    auto issue = [&](int r) -> Quad4 {
-        Quad4 u;
-        u.v0 = lds_read16(tb, sdwa_shl_word0(four, pa[r]));
-        u.v1 = lds_read16(tb, sdwa_shl_word1(four, pa[r]) + PLANE);
-        u.v2 = lds_read16(tb, sdwa_shl_word0(four, pb[r]));
-        u.v3 = lds_read16(tb, sdwa_shl_word1(four, pb[r]) + PLANE);
-        return u;
-    };
-    auto consume = [&](const Quad4& u, int r, int t) {
-        float sx = u.v0.x + u.v1.x, sy = u.v0.y + u.v1.y, sz = u.v0.z + u.v1.z, sw = u.v0.w + u.v1.w;
-        sx = sx + u.v2.x; sy = sy + u.v2.y; sz = sz + u.v2.z; sw = sw + u.v2.w;
-        sx = sx + u.v3.x; sy = sy + u.v3.y; sz = sz + u.v3.z; sw = sw + u.v3.w;
-        float m4 = __builtin_fminf(__builtin_fminf(sx, sy), __builtin_fminf(sz, sw));
-        tix[r] = (m4 < best[r]) ? t : tix[r];
-        best[r] = __builtin_fminf(best[r], m4);
-    };
-
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();                       // everyone is done reading the previous tile
-        if (PREFETCH) {
-#pragma unroll
-            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
-        } else {
-            v4f tmp[NF];
-#pragma unroll
-            for (int i = 0; i < NF; ++i) tmp[i] = gload(t, i);
-#pragma unroll
-            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = tmp[i];
-        }
-        __syncthreads();
-        if (PREFETCH) {
-            // the last iteration re-reads its own tile: a harmless, unconditional load
-            const int tn = t + 1 < ntiles ? t + 1 : t;
-#pragma unroll
-            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
-        }
-        Quad4 ua = issue(0);
-#pragma unroll
-        for (int r = 0; r < R; r += 2) {
-            Quad4 ub = issue(r + 1);
-            consume(ua, r, t);
-            if (r + 2 < R) ua = issue(r + 2);
-            consume(ub, r + 1, t);
-        }
-    }
-
-    // recover the center index inside the winning tile, then merge the 8 lanes of the slot.
-    // Codes are handled four at a time so that their 16 global loads are in flight together.
-    constexpr int G = 4;
-    static_assert(R % G == 0, "the epilogue handles codes in groups of four");
-#pragma unroll 1
-    for (int r0 = 0; r0 < R; r0 += G) {
-        v4f w[G][4];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            // r0 is a run-time value here: select this group's state without dynamic register indexing
-            uint32_t a = 0, b2 = 0;
-            int tx = 0;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tx = tix[r]; }
-            const char* gbase = reinterpret_cast<const char*>(img + (size_t)(tx < 0 ? 0 : tx) * TILE_F4);
-            w[g][0] = *reinterpret_cast<const v4f*>(gbase + ((a & 0xffffu) << 4));
-            w[g][1] = *reinterpret_cast<const v4f*>(gbase + ((a >> 16) << 4) + PLANE);
-            w[g][2] = *reinterpret_cast<const v4f*>(gbase + ((b2 & 0xffffu) << 4));
-            w[g][3] = *reinterpret_cast<const v4f*>(gbase + ((b2 >> 16) << 4) + PLANE);
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float b = INFINITY;
-            int tx = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { b = best[r]; tx = tix[r]; }
-            int bi = IDX_NONE;
-            v4f sv = w[g][0] + w[g][1];
-            sv = sv + w[g][2];
-            sv = sv + w[g][3];
-            if (tx >= 0) {
-                const int kb = tx * TK + q * 4;
-                const float bb = b;
-                if (sv.w == bb) { bi = kb + 3; b = sv.w; }
-                if (sv.z == bb) { bi = kb + 2; b = sv.z; }
-                if (sv.y == bb) { bi = kb + 1; b = sv.y; }
-                if (sv.x == bb) { bi = kb; b = sv.x; }
-            }
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
-                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-            }
-            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
-            if (q == 0 && n < N) {
-                assign[n] = (bi == IDX_NONE) ? 0 : bi;
-                if (dist) dist[n] = b;
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// M = 4 scan with 4 lanes per slot: each lane owns 8 of the tile's 32 centers (two 16-byte reads
-// per subspace, the two halves of the 128-byte row), which halves the number of lanes that must
-// replicate a code's state, so a workgroup holds twice as many codes per tile fill (C = 128*R at
-// 512 threads).  Slots of odd index read the upper half-row first, which spreads the four slots
-// of a 16-lane LDS access group over the banks.  Because only the minimum over the lane's 8
-// centers and the tile index are tracked, the order in which a lane meets its centers inside a
-// tile does not matter; the epilogue re-derives the winner inside the winning tile in ascending
-// center order.
-// ---------------------------------------------------------------------------------------------
-template <int R, int THREADS, bool PREFETCH>
-__global__ __launch_bounds__(THREADS) void assign_scan4x2_kernel(const uint8_t* __restrict__ codes, int64_t N,
-                                                                 const float4* __restrict__ img, int ntiles,
-                                                                 int32_t* __restrict__ assign,
-                                                                 float* __restrict__ dist)
-{
-    constexpr int LPS = 4, TK = 32;
-    constexpr int SLOTS = THREADS / LPS;
-    constexpr int C = SLOTS * R;
-    constexpr int NF = TILE_F4 / THREADS;
-    constexpr int PLANE = 32768;
-
-    __shared__ float4 tile[TILE_F4];
-    const char* tb = reinterpret_cast<const char*>(tile);
-
-    const int tid = threadIdx.x;
-    const int q = tid % LPS;
-    const int c = tid / LPS;
-    const uint32_t par = (uint32_t)c & 1u;         // odd slots start with the upper half-row
-    const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
-
-    uint32_t pa[R], pb[R];
-    float best[R];
-    int tix[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        int64_t n = base + (int64_t)r * SLOTS + c;
-        if (n >= N) n = N - 1;
-        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
-        const uint32_t lo = (par << 2) | (uint32_t)q;               // (par*64 + q*16) / 16
-        uint32_t f0 = ((pk & 255u) << 3) | lo;
-        uint32_t f1 = (((pk >> 8) & 255u) << 3) | lo;
-        uint32_t f2 = ((((pk >> 16) & 255u) << 3) | lo) + 4096u;
-        uint32_t f3 = (((pk >> 24) << 3) | lo) + 4096u;
-        pa[r] = f0 | (f1 << 16);
-        pb[r] = f2 | (f3 << 16);
-        best[r] = INFINITY;
-        tix[r] = -1;
-    }
-
-    const uint32_t lane_off = (uint32_t)tid * 16u;
-    v4f* ltile = reinterpret_cast<v4f*>(tile);
-    auto gload = [&](int t, int i) -> v4f {
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
-        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
-    };
-    v4f pf[NF];
-    if (PREFETCH) {
-#pragma unroll
-        for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
-    }
-
-    // one unit of work = (code r, half h): 4 reads, one per subspace.  The four row offsets are
-    // unpacked once per code; the second half-row is the first one with bit 6 flipped.
-    struct Addr4 { uint32_t a0, a1, a2, a3; };
-    auto unpack = [&](int r) -> Addr4 {
-        Addr4 a;
-        a.a0 = sdwa_shl_word0(four, pa[r]);
-        a.a1 = sdwa_shl_word1(four, pa[r]);
-        a.a2 = sdwa_shl_word0(four, pb[r]);
-        a.a3 = sdwa_shl_word1(four, pb[r]);
-        return a;
-    };
-    auto issue = [&](const Addr4& a, int h) -> Quad4 {
-        Quad4 u;
-        const uint32_t flip = h ? 64u : 0u;
-        u.v0 = lds_read16(tb, a.a0 ^ flip);
-        u.v1 = lds_read16(tb, (a.a1 ^ flip) + PLANE);
-        u.v2 = lds_read16(tb, a.a2 ^ flip);
-        u.v3 = lds_read16(tb, (a.a3 ^ flip) + PLANE);
-        return u;
-    };
-    auto min4 = [&](const Quad4& u) -> float {
-        float sx = u.v0.x + u.v1.x, sy = u.v0.y + u.v1.y, sz = u.v0.z + u.v1.z, sw = u.v0.w + u.v1.w;
-        sx = sx + u.v2.x; sy = sy + u.v2.y; sz = sz + u.v2.z; sw = sw + u.v2.w;
-        sx = sx + u.v3.x; sy = sy + u.v3.y; sz = sz + u.v3.z; sw = sw + u.v3.w;
-        return __builtin_fminf(__builtin_fminf(sx, sy), __builtin_fminf(sz, sw));
-    };
-
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-        if (PREFETCH) {
-#pragma unroll
-            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
-        } else {
-            v4f tmp[NF];
-#pragma unroll
-            for (int i = 0; i < NF; ++i) tmp[i] = gload(t, i);
-#pragma unroll
-            for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = tmp[i];
-        }
-        __syncthreads();
-        if (PREFETCH) {
-            const int tn = t + 1 < ntiles ? t + 1 : t;
-#pragma unroll
-            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
-        }
-        Addr4 ad = unpack(0);
-        Quad4 ua = issue(ad, 0);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            Quad4 ub = issue(ad, 1);
-            float m8 = min4(ua);
-            if (r + 1 < R) {
-                ad = unpack(r + 1);
-                ua = issue(ad, 0);
-            }
-            m8 = __builtin_fminf(m8, min4(ub));
-            tix[r] = (m8 < best[r]) ? t : tix[r];
-            best[r] = __builtin_fminf(best[r], m8);
-        }
-    }
-
-    // Epilogue: recover the center inside the winning tile, then merge the 4 lanes of the slot.
-    // Only lanes whose minimum equals the slot's minimum can hold the winner, so only they re-read
-    // their 8 sums from the tile image (scattered 16-byte reads: the fewer the better).
-    constexpr int G = THREADS > 512 ? 2 : 4;
-    static_assert(R % G == 0, "the epilogue handles codes in groups");
-#pragma unroll 1
-    for (int r0 = 0; r0 < R; r0 += G) {
-        v4f w[G][8];
-        float bq[G];
-        int tq[G];
-        bool need[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint32_t a = 0, b2 = 0;
-            bq[g] = INFINITY;
-            tq[g] = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
-            float smin = bq[g];
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
-            need[g] = tq[g] >= 0 && bq[g] == smin;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
-            if (need[g]) {
-                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
-                const uint32_t o0 = (a & 0xffffu) << 4, o1 = ((a >> 16) << 4) + PLANE;
-                const uint32_t o2 = (b2 & 0xffffu) << 4, o3 = ((b2 >> 16) << 4) + PLANE;
-                // w[g][0..3]: the lower half-row (centers 4q..4q+3), w[g][4..7]: the upper one (16+4q..)
-                const uint32_t lowsel = par ? 64u : 0u;     // this lane's stored offsets point at half `par`
-                w[g][0] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel));
-                w[g][1] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel));
-                w[g][2] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel));
-                w[g][3] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel));
-                w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 ^ lowsel ^ 64u));
-                w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 ^ lowsel ^ 64u));
-                w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 ^ lowsel ^ 64u));
-                w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 ^ lowsel ^ 64u));
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float b = INFINITY;
-            int bi = IDX_NONE;
-            v4f lo = w[g][0] + w[g][1];
-            lo = lo + w[g][2];
-            lo = lo + w[g][3];
-            v4f hi = w[g][4] + w[g][5];
-            hi = hi + w[g][6];
-            hi = hi + w[g][7];
-            if (need[g]) {
-                const int kb = tq[g] * TK + q * 4;
-                const float bb = bq[g];
-                b = bb;
-                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
-                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
-                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
-                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
-                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
-                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
-                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
-                if (lo.x == bb) { bi = kb; b = lo.x; }
-            }
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
-                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-            }
-            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
-            if (q == 0 && n < N) {
-                assign[n] = (bi == IDX_NONE) ? 0 : bi;
-                if (dist) dist[n] = b;
-            }
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // M = 4 scan with conflict-free LDS reads ("subspace skew").
 //
-// Same decomposition as assign_scan4x2_kernel (4 lanes per slot, 8 centers per lane, TK = 32),
-// but the tile image is x-major -- row (x, m) at byte x*512 + m*128 -- so that a row's LDS bank
+// TK = 32 centers per tile; 4 lanes form a slot and each lane owns 8 of the tile's centers (two
+// 16-byte reads per subspace, the two halves of the 128-byte row), so a workgroup of T threads
+// holds T/4 * R codes per tile fill.  Only the minimum over the lane's 8 centers and the tile
+// index are tracked, so the order in which a lane meets its centers inside a tile does not matter.
+// The tile image is x-major -- row (x, m) at byte x*512 + m*128 -- so that a row's LDS bank
 // half is the parity of m and its quarter the half-row.  A 16-byte-per-lane LDS read is served
 // 16 lanes = 4 slots per clock; the four slots of a group are made to hit four different bank
 // quarters in every read: slots 0,1 of the group read subspace i in step i, slots 2,3 read
@@ -797,8 +436,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* _
         }
     }
 
-    // Epilogue: as in assign_scan4x2_kernel; the four real subspace offsets are fields 0..3 (early
-    // slots) or 1..4 (late slots), and an offset is the byte position inside the tile image.
+    // Epilogue: recover the center inside the winning tile, then merge the 4 lanes of the slot.  Only lanes whose
+    // minimum equals the slot's minimum can hold the winner, so only they re-read their sums' terms from the tile
+    // image.  The four real subspace offsets are fields 0..3 (early slots) or 1..4 (late slots), and an offset is
+    // the byte position inside the tile image.
     constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
     static_assert(R % G == 0, "the epilogue handles codes in groups");
 #pragma unroll 1
@@ -875,200 +516,6 @@ __global__ __launch_bounds__(THREADS) void assign_scan4s_kernel(const uint8_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
-// The same scan with the reads of a whole code in flight ahead of the sums (deeper software pipeline).
-template <int R, int THREADS>
-__global__ __launch_bounds__(THREADS) void assign_scan4sd_kernel(const uint8_t* __restrict__ codes, int64_t N,
-                                                                const float4* __restrict__ img, int ntiles,
-                                                                int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist)
-{
-    constexpr int LPS = 4, TK = 32;
-    constexpr int SLOTS = THREADS / LPS;
-    constexpr int C = SLOTS * R;
-    constexpr int NF = (TILE_F4 + THREADS - 1) / THREADS;     // float4 per thread per tile fill (last one partial)
-    constexpr bool EVEN = TILE_F4 % THREADS == 0;
-    constexpr uint32_t PAD = TILE_BYTES;      // 256 bytes of -0.0: [PAD, PAD+128) in bank half 0, the rest in half 1
-
-    __shared__ float4 tile[TILE_F4 + 16];
-    const char* tb = reinterpret_cast<const char*>(tile);
-
-    const int tid = threadIdx.x;
-    const int q = tid % LPS;
-    const int c = tid / LPS;
-    const uint32_t hsel = (uint32_t)c & 1u;           // odd slots start with the upper half-row
-    const uint32_t late = ((uint32_t)c >> 1) & 1u;    // slots 2,3 of a group run one subspace behind
-    const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
-
-    if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
-
-    // five step offsets per code, /16, in 16-bit fields: pa = f0|f1, pb = f2|f3; the fifth fields of
-    // codes 2i and 2i+1 share pc[i]
-    static_assert(R % 2 == 0, "fifth offsets are stored two to a register");
-    uint32_t pa[R], pb[R], pc[R / 2];
-    float best[R];
-    int tix[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        int64_t n = base + (int64_t)r * SLOTS + c;
-        if (n >= N) n = N - 1;
-        uint32_t pk = *reinterpret_cast<const uint32_t*>(codes + n * 4);
-        const uint32_t lo = (hsel << 2) | (uint32_t)q;                       // (hsel*64 + q*16) / 16
-        uint32_t g0 = ((pk & 255u) << 5) | (0u << 3) | lo;                   // (x*512 + m*128)/16 = x*32 + m*8
-        uint32_t g1 = (((pk >> 8) & 255u) << 5) | (1u << 3) | lo;
-        uint32_t g2 = (((pk >> 16) & 255u) << 5) | (2u << 3) | lo;
-        uint32_t g3 = ((pk >> 24) << 5) | (3u << 3) | lo;
-        uint32_t dz = (PAD >> 4) + ((late ^ 1u) ? 0u : 8u) + lo;             // early slots pad in half 0, late ones in half 1
-        uint32_t f0 = late ? dz : g0, f1 = late ? g0 : g1, f2 = late ? g1 : g2, f3 = late ? g2 : g3,
-                 f4 = late ? g3 : dz;
-        pa[r] = f0 | (f1 << 16);
-        pb[r] = f2 | (f3 << 16);
-        if (r & 1) pc[r / 2] |= f4 << 16; else pc[r / 2] = f4;
-        best[r] = INFINITY;
-        tix[r] = -1;
-    }
-
-    const uint32_t lane_off = (uint32_t)tid * 16u;
-    v4f* ltile = reinterpret_cast<v4f*>(tile);
-    auto gload = [&](int t, int i) -> v4f {
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
-        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
-    };
-    v4f pf[NF];
-#pragma unroll
-    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
-
-    // all ten reads of code r+1 (five steps, two half-rows each) are in flight while code r is summed
-    struct Set { float4 a[5], b[5]; };
-    auto issue = [&](int r) -> Set {
-        Set u;
-#pragma unroll
-        for (int i = 0; i < 5; ++i) {
-            uint32_t ad = (i == 0) ? sdwa_shl_word0(four, pa[r])
-                        : (i == 1) ? sdwa_shl_word1(four, pa[r])
-                        : (i == 2) ? sdwa_shl_word0(four, pb[r])
-                        : (i == 3) ? sdwa_shl_word1(four, pb[r])
-                        : (r & 1)  ? sdwa_shl_word1(four, pc[r / 2])
-                                   : sdwa_shl_word0(four, pc[r / 2]);
-            u.a[i] = lds_read16(tb, ad);
-            u.b[i] = lds_read16(tb, ad ^ 64u);
-        }
-        return u;
-    };
-    auto consume = [&](const Set& u, int r, int t) {
-        float4 sa = u.a[0], sb = u.b[0];
-#pragma unroll
-        for (int i = 1; i < 5; ++i) {
-            sa.x = sa.x + u.a[i].x; sa.y = sa.y + u.a[i].y; sa.z = sa.z + u.a[i].z; sa.w = sa.w + u.a[i].w;
-            sb.x = sb.x + u.b[i].x; sb.y = sb.y + u.b[i].y; sb.z = sb.z + u.b[i].z; sb.w = sb.w + u.b[i].w;
-        }
-        float m8 = min3_f32(sa.x, sa.y, sa.z);
-        m8 = min3_f32(m8, sa.w, sb.x);
-        m8 = min3_f32(m8, sb.y, sb.z);
-        const float nb = min3_f32(m8, sb.w, best[r]);
-        tix[r] = (nb < best[r]) ? t : tix[r];
-        best[r] = nb;
-    };
-
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NF; ++i)
-            if (EVEN || i * THREADS + tid < TILE_F4) ltile[i * THREADS + tid] = pf[i];
-        __syncthreads();
-        // the loads of the next tile are spread over the first 5/8 of the scan
-        const int tn = t + 1 < ntiles ? t + 1 : t;
-        Set cur = issue(0);
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-#pragma unroll
-            for (int i = 0; i < NF; ++i)
-                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
-            Set nxt = cur;
-            if (r + 1 < R) nxt = issue(r + 1);
-            consume(cur, r, t);
-            cur = nxt;
-        }
-    }
-
-    // Epilogue: as in assign_scan4x2_kernel; the four real subspace offsets are fields 0..3 (early
-    // slots) or 1..4 (late slots), and an offset is the byte position inside the tile image.
-    constexpr int G = THREADS > 768 ? 1 : (THREADS > 512 ? 2 : 4);
-    static_assert(R % G == 0, "the epilogue handles codes in groups");
-#pragma unroll 1
-    for (int r0 = 0; r0 < R; r0 += G) {
-        v4f w[G][8];
-        float bq[G];
-        int tq[G];
-        bool need[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint32_t a = 0, b2 = 0, c2 = 0;
-            bq[g] = INFINITY;
-            tq[g] = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; c2 = (r & 1) ? pc[r / 2] >> 16 : pc[r / 2]; tq[g] = tix[r]; bq[g] = best[r]; }
-            float smin = bq[g];
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
-            need[g] = tq[g] >= 0 && bq[g] == smin;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
-            if (need[g]) {
-                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * TILE_F4);
-                const uint32_t e0 = a & 0xffffu, e1 = a >> 16, e2 = b2 & 0xffffu, e3 = b2 >> 16, e4 = c2 & 0xffffu;
-                const uint32_t o0 = ((late ? e1 : e0) << 4) & ~64u, o1 = ((late ? e2 : e1) << 4) & ~64u;
-                const uint32_t o2 = ((late ? e3 : e2) << 4) & ~64u, o3 = ((late ? e4 : e3) << 4) & ~64u;
-                w[g][0] = *reinterpret_cast<const v4f*>(gbase + o0);
-                w[g][1] = *reinterpret_cast<const v4f*>(gbase + o1);
-                w[g][2] = *reinterpret_cast<const v4f*>(gbase + o2);
-                w[g][3] = *reinterpret_cast<const v4f*>(gbase + o3);
-                w[g][4] = *reinterpret_cast<const v4f*>(gbase + (o0 | 64u));
-                w[g][5] = *reinterpret_cast<const v4f*>(gbase + (o1 | 64u));
-                w[g][6] = *reinterpret_cast<const v4f*>(gbase + (o2 | 64u));
-                w[g][7] = *reinterpret_cast<const v4f*>(gbase + (o3 | 64u));
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float b = INFINITY;
-            int bi = IDX_NONE;
-            v4f lo = w[g][0] + w[g][1];
-            lo = lo + w[g][2];
-            lo = lo + w[g][3];
-            v4f hi = w[g][4] + w[g][5];
-            hi = hi + w[g][6];
-            hi = hi + w[g][7];
-            if (need[g]) {
-                const int kb = tq[g] * TK + q * 4;
-                const float bb = bq[g];
-                b = bb;
-                if (hi.w == bb) { bi = kb + 19; b = hi.w; }
-                if (hi.z == bb) { bi = kb + 18; b = hi.z; }
-                if (hi.y == bb) { bi = kb + 17; b = hi.y; }
-                if (hi.x == bb) { bi = kb + 16; b = hi.x; }
-                if (lo.w == bb) { bi = kb + 3; b = lo.w; }
-                if (lo.z == bb) { bi = kb + 2; b = lo.z; }
-                if (lo.y == bb) { bi = kb + 1; b = lo.y; }
-                if (lo.x == bb) { bi = kb; b = lo.x; }
-            }
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
-                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-            }
-            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
-            if (q == 0 && n < N) {
-                assign[n] = (bi == IDX_NONE) ? 0 : bi;
-                if (dist) dist[n] = b;
-            }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Regrouping of M = 4 codes for the conflict-free scans below.
 //
@@ -1326,7 +773,7 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
 // ---------------------------------------------------------------------------------------------
 // M = 4 scan over residue-grouped codes ("half-plane" tile image).
 //
-// Same decomposition as assign_scan4x2_kernel (4 lanes per slot, 8 centers per lane, TK = 32),
+// Same decomposition as assign_scan4s_kernel (4 lanes per slot, 8 centers per lane, TK = 32),
 // but the tile image is stored as eight planes, one per (subspace m, half h of the tile's
 // centers): the 64 bytes of centers 16h .. 16h+15 for subcode x sit at byte
 //      (2m + h) * 16384 + x * 64,
@@ -1589,184 +1036,6 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
-// M = 4 scan over residue-grouped codes, 16-center tiles.
-//
-// The tile is 16 centers (64 KB: img16[tile][m][x][16]), so two workgroups share a compute unit
-// and one scans while the other refills its tile between barriers.  4 lanes per slot, 4 centers
-// per lane: one 16-byte read per subspace and code at byte m*16384 + x*64 + 16q; the plane
-// offset is the instruction's immediate.  As in assign_scan4p_kernel the read is conflict-free
-// when the codes whose lanes the LDS serves together have four different subcodes mod 4, and
-// the caller passes regrouped codes with their original positions.  The reads of DEPTH codes
-// are in flight while the sums of the current one are formed.
-// ---------------------------------------------------------------------------------------------
-template <int R, int THREADS, int DEPTH>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(THREADS / 128, THREADS / 128)))
-void assign_scan4q_kernel(const uint8_t* __restrict__ codes, int64_t N,
-                                                                const uint2* __restrict__ gco,
-                                                                const float4* __restrict__ img, int ntiles,
-                                                                int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist)
-{
-    constexpr int LPS = 4, TK = 16;
-    constexpr int SLOTS = THREADS / LPS;
-    constexpr int C = SLOTS * R;
-    constexpr int T16_F4 = TILE_F4 / 2, T16_BYTES = TILE_BYTES / 2;
-    constexpr int NF = T16_F4 / THREADS;
-    constexpr uint32_t PLANE = 16384;       // bytes per subspace plane: 256 subcodes x 16 centers
-    static_assert(T16_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
-    static_assert(R % DEPTH == 0 && R >= 2 * DEPTH, "codes are consumed in rounds of DEPTH");
-
-    __shared__ float4 tile[T16_F4];
-    const char* tb = reinterpret_cast<const char*>(tile);
-
-    const int tid = threadIdx.x;
-    const int q = tid % LPS;
-    const int c = tid / LPS;
-    const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
-
-    uint32_t pa[R], pb[R];      // 16-bit fields (x_m*64 + 16q) / 16
-    float best[R];
-    int tix[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        int64_t n = base + (int64_t)r * SLOTS + c;
-        if (n >= N) n = N - 1;
-        uint32_t pk = gco ? gco[n].x : *reinterpret_cast<const uint32_t*>(codes + n * 4);
-        uint32_t f0 = ((pk & 255u) << 2) | (uint32_t)q;
-        uint32_t f1 = (((pk >> 8) & 255u) << 2) | (uint32_t)q;
-        uint32_t f2 = (((pk >> 16) & 255u) << 2) | (uint32_t)q;
-        uint32_t f3 = ((pk >> 24) << 2) | (uint32_t)q;
-        pa[r] = f0 | (f1 << 16);
-        pb[r] = f2 | (f3 << 16);
-        best[r] = INFINITY;
-        tix[r] = -1;
-    }
-
-    const uint32_t lane_off = (uint32_t)tid * 16u;
-    v4f* ltile = reinterpret_cast<v4f*>(tile);
-    auto gload = [&](int t, int i) -> v4f {
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float4*>(img + (size_t)t * T16_F4), 0, T16_BYTES, 0x00020000);
-        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
-    };
-    v4f pf[NF];
-#pragma unroll
-    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
-
-    struct Set { float4 v[4]; };
-    auto issue = [&](int r) -> Set {
-        Set u;
-        u.v[0] = lds_read16(tb, sdwa_shl_word0(four, pa[r]));
-        u.v[1] = lds_read16(tb, sdwa_shl_word1(four, pa[r]) + PLANE);
-        u.v[2] = lds_read16(tb, sdwa_shl_word0(four, pb[r]) + 2 * PLANE);
-        u.v[3] = lds_read16(tb, sdwa_shl_word1(four, pb[r]) + 3 * PLANE);
-        return u;
-    };
-    auto consume = [&](const Set& u, int r, int t) {
-        float4 s = u.v[0];
-#pragma unroll
-        for (int m = 1; m < 4; ++m) {
-            s.x = s.x + u.v[m].x; s.y = s.y + u.v[m].y; s.z = s.z + u.v[m].z; s.w = s.w + u.v[m].w;
-        }
-        const float m4 = min3_f32(s.x, s.y, s.z);
-        const float nb = min3_f32(m4, s.w, best[r]);
-        tix[r] = (nb < best[r]) ? t : tix[r];
-        best[r] = nb;
-    };
-
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
-        __syncthreads();
-        // the loads of the next tile are spread over the first 5/8 of the scan (see assign_scan4p_kernel)
-        const int tn = t + 1 < ntiles ? t + 1 : t;
-        Set ring[DEPTH];
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
-#pragma unroll
-        for (int r0 = 0; r0 < R; r0 += DEPTH) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-#pragma unroll
-                for (int i = 0; i < NF; ++i)
-                    if ((i * R * 5) / (NF * 8) == r0 + d) pf[i] = gload(tn, i);
-                const Set u = ring[d];
-                if (r0 + DEPTH + d < R) ring[d] = issue(r0 + DEPTH + d);
-                consume(u, r0 + d, t);
-            }
-        }
-    }
-
-    // Epilogue: recover the center inside the winning tile (re-read from the image, same bits and sum
-    // order), then merge the 4 lanes of the slot by (value, index).
-    constexpr int G = THREADS > 512 ? 2 : 4;
-    static_assert(R % G == 0, "the epilogue handles codes in groups");
-#pragma unroll 1
-    for (int r0 = 0; r0 < R; r0 += G) {
-        v4f w[G][4];
-        float bq[G];
-        int tq[G];
-        bool need[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            uint32_t a = 0, b2 = 0;
-            bq[g] = INFINITY;
-            tq[g] = -1;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r == r0 + g) { a = pa[r]; b2 = pb[r]; tq[g] = tix[r]; bq[g] = best[r]; }
-            float smin = bq[g];
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) smin = __builtin_fminf(smin, __shfl_xor(smin, d));
-            need[g] = tq[g] >= 0 && bq[g] == smin;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) w[g][i] = v4f{INFINITY, INFINITY, INFINITY, INFINITY};
-            if (need[g]) {
-                const char* gbase = reinterpret_cast<const char*>(img + (size_t)tq[g] * T16_F4);
-                w[g][0] = *reinterpret_cast<const v4f*>(gbase + ((a & 0xffffu) << 4));
-                w[g][1] = *reinterpret_cast<const v4f*>(gbase + ((a >> 16) << 4) + PLANE);
-                w[g][2] = *reinterpret_cast<const v4f*>(gbase + ((b2 & 0xffffu) << 4) + 2 * PLANE);
-                w[g][3] = *reinterpret_cast<const v4f*>(gbase + ((b2 >> 16) << 4) + 3 * PLANE);
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float b = INFINITY;
-            int bi = IDX_NONE;
-            v4f sv = w[g][0] + w[g][1];
-            sv = sv + w[g][2];
-            sv = sv + w[g][3];
-            if (need[g]) {
-                const int kb = tq[g] * TK + q * 4;
-                const float bb = bq[g];
-                b = bb;
-                if (sv.w == bb) { bi = kb + 3; b = sv.w; }
-                if (sv.z == bb) { bi = kb + 2; b = sv.z; }
-                if (sv.y == bb) { bi = kb + 1; b = sv.y; }
-                if (sv.x == bb) { bi = kb; b = sv.x; }
-            }
-#pragma unroll
-            for (int d = LPS / 2; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
-                if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
-            }
-            int64_t n = base + (int64_t)(r0 + g) * SLOTS + c;
-            if (q == 0 && n < N) {
-                const uint32_t og = gco ? gco[n].y : 0u;
-                const int64_t dst = gco ? (int64_t)og : n;
-                if (og != ORIGIN_NONE) {
-                    assign[dst] = (bi == IDX_NONE) ? 0 : bi;
-                    if (dist) dist[dst] = b;
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Subspace-skewed scan for M = 8, 16, 32 (64-bit SIFT-like codes, CNN-feature codes; Sec. 4).
 //
 // All M subspaces of TK = 128/M centers are resident (x-major image: row (x, m) of TK*4 bytes at
@@ -1781,7 +1050,7 @@ void assign_scan4q_kernel(const uint8_t* __restrict__ codes, int64_t N,
 // one SDWA shift per read); minimum tracking, prefetch of the next tile and the epilogue are
 // those of the M = 4 kernels (the epilogue rebuilds its offsets from the code bytes).
 // ---------------------------------------------------------------------------------------------
-template <int M, int R, int THREADS>
+template <int M, int R, int THREADS, int DEPTH = 1>
 __global__ __launch_bounds__(THREADS) void assign_scan_skew_kernel(const uint8_t* __restrict__ codes, int64_t N,
                                                                    const float4* __restrict__ img, int ntiles,
                                                                    int32_t* __restrict__ assign,
@@ -1853,31 +1122,34 @@ __global__ __launch_bounds__(THREADS) void assign_scan_skew_kernel(const uint8_t
 #pragma unroll
         for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
         __syncthreads();
-        {
-            const int tn = t + 1 < ntiles ? t + 1 : t;
+        // the loads of the next tile are spread over the first 5/8 of the scan (a burst of them would hold every
+        // wave in the vector-memory queue while the LDS pipe idles); the reads of the next DEPTH steps are in
+        // flight while the current one is added
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        float4 ring[DEPTH];
 #pragma unroll
-            for (int i = 0; i < NF; ++i) pf[i] = gload(tn, i);
-        }
-        float4 cur = issue(0, 0);
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d / STEPS, d % STEPS);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
             float4 sa;
 #pragma unroll
             for (int i = 0; i < STEPS; ++i) {
-                float4 nxt = cur;
-                if (i + 1 < STEPS) nxt = issue(r, i + 1);
-                else if (r + 1 < R) nxt = issue(r + 1, 0);
+                const int step = r * STEPS + i;
+                const float4 cur = ring[step % DEPTH];
+                if (step + DEPTH < R * STEPS) ring[step % DEPTH] = issue((step + DEPTH) / STEPS, (step + DEPTH) % STEPS);
                 if (i == 0) {
                     sa = cur;
                 } else {
                     sa.x = sa.x + cur.x; sa.y = sa.y + cur.y; sa.z = sa.z + cur.z; sa.w = sa.w + cur.w;
                 }
-                cur = nxt;
             }
-            float m4 = __builtin_fminf(__builtin_fminf(sa.x, sa.y), sa.z);
-            m4 = __builtin_fminf(m4, sa.w);
-            tix[r] = (m4 < best[r]) ? t : tix[r];
-            best[r] = __builtin_fminf(best[r], m4);
+            const float m4 = min3_f32(sa.x, sa.y, sa.z);
+            const float nb = min3_f32(m4, sa.w, best[r]);
+            tix[r] = (nb < best[r]) ? t : tix[r];
+            best[r] = nb;
         }
     }
 
