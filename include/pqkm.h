@@ -18,7 +18,8 @@
  *     the end of the enqueued work.
  *   - `workspace` is device scratch of at least
  *     pqkm_workspace_bytes(N, M, K) bytes, 256-byte aligned, used only during
- *     the call's enqueued work.  Two calls that overlap in time on different
+ *     the call's enqueued work (tile images of the centers, for M = 4 a
+ *     regrouped copy of the codes of one scan launch, histograms).  Two calls that overlap in time on different
  *     streams need different workspaces.
  *   - Subcode/center indices are 0..255 (the paper's 1..L with L = 256,
  *     Sec. 2.2).  `codes` must be 4-byte aligned when M is a multiple of 4.
@@ -150,8 +151,10 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
  *   "assign_kernel"      0 = choose automatically (default), 1 = force the generic
  *                        scan that reads the tables through the cache hierarchy,
  *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
- *   "scan_variant"       0 = default launch shape of the LDS-tiled scan, 1..99 =
- *                        one specific compiled shape (for tuning sweeps)
+ *   "scan_variant"       0 = default scan of the LDS-tiled assignment (for M = 4: codes regrouped for
+ *                        conflict-free LDS reads when N >= 65536 and K >= 128, else the subspace-skewed
+ *                        scan), 1..99 = one specific compiled scan and launch shape (for tuning sweeps;
+ *                        e.g. 34 = the skewed M = 4 scan without regrouping, 70 = the regrouped one)
  *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
  *                        per code and subspace, 2 = force the LDS-privatised histogram
  *   "hist_groups"        target number of cluster groups of the LDS-privatised histogram,

@@ -132,6 +132,34 @@ def test_assign_regrouped_scan(env, variant, kind, N):
         _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
 
 
+def test_regrouped_scan_in_several_launches(env):
+    """Scan launches smaller than N: every launch regroups its own stretch of the codes, and pqkm_fit cannot keep
+    the regrouped copy between iterations (it holds one launch only)."""
+    pq, oracle, W, torch = env["pq"], env["oracle"], env["W"], env["torch"]
+    w = workload(2, N=300_001, K=257, T=500)
+    codes = W.codes_numpy(w)
+    centers = codes[W.init_center_indices(w)].copy()
+    tables = oracle.build_tables(W.codewords(w))
+    pq.set_option("launch_codes_log2", 17)            # 131072 codes per launch: 3 launches, the last one ragged
+    try:
+        a, d = pq.assign(_dev(env, codes), _dev(env, centers), _dev(env, tables))
+        cen = _dev(env, centers)
+        gh = torch.empty((257, 4, 256), dtype=torch.int32, device=env["dev"])
+        gc = torch.empty(257, dtype=torch.int32, device=env["dev"])
+        _, ga = pq.fit(_dev(env, codes), _dev(env, tables), cen, 3, hist=gh, counts=gc)
+        _sync(env)
+    finally:
+        pq.set_option("launch_codes_log2", 26)
+    ra, rd = oracle.assign(codes, centers, tables)
+    np.testing.assert_array_equal(a.cpu().numpy(), ra)
+    np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+    rc, rfa, rh, rcnt = oracle.fit(codes, tables, centers, 3)
+    np.testing.assert_array_equal(cen.cpu().numpy(), rc)
+    np.testing.assert_array_equal(ga.cpu().numpy(), rfa)
+    np.testing.assert_array_equal(gh.cpu().numpy().view(np.uint32), rh)
+    np.testing.assert_array_equal(gc.cpu().numpy().view(np.uint32), rcnt)
+
+
 @pytest.mark.parametrize("M,variant", [(8, 0), (8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (16, 0), (16, 1), (16, 2), (16, 3),
                                        (16, 4), (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5)])
 def test_assign_every_compiled_shape_wide_codes(env, M, variant):
