@@ -35,7 +35,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, gco_off, plan_off, rows_off, total;
+        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -95,6 +95,14 @@ Carve carve(int64_t N, int M, int K)
         off += align256((size_t)na * sizeof(uint2));
         c.plan_off = off;
         off += align256(sizeof(GroupPlan));
+    }
+    c.gc8_off = c.plan8_off = off;
+    if (M == 8) {
+        const int64_t na = group_alloc(N < GROUP_CHUNK_MAX ? N : GROUP_CHUNK_MAX);
+        c.gc8_off = off;
+        off += align256((size_t)na * sizeof(uint4));
+        c.plan8_off = off;
+        off += align256(sizeof(GroupPlan8));
     }
     c.total = off;
     return c;
@@ -178,7 +186,18 @@ inline int variant_layout(int M, int variant)
         if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79)) return 2;
         return (variant >= 30 && variant <= 39) ? 1 : 0;
     }
-    return variant != 1 ? 1 : 0;  // M = 8, 16, 32: every shape but 1 (the unskewed tiled scan) is skewed
+    if (M == 8 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 0;   // [m][x][k]
+    return variant != 1 ? 1 : 0;  // M = 8, 16, 32: every other shape but 1 (the unskewed tiled scan) is skewed
+}
+
+template <int R, int THREADS, int DEPTH>
+void launch_scan8p(const uint8_t* codes, int64_t N, const uint4* gc8, const float4* img, int ntiles, int32_t* assign,
+                   float* dist, hipStream_t st)
+{
+    constexpr int C = (THREADS / 4) * R;
+    int64_t nwg = (N + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan8p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
+                       gc8, img, ntiles, assign, dist);
 }
 
 template <int M>
@@ -194,6 +213,31 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
         case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
         default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;   // 70
     }
+}
+
+// M = 8 scans over regrouped codes: variants 70..79
+void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
+                          float* dist, hipStream_t st)
+{
+    switch (variant) {
+        case 71: launch_scan8p<12, 1024, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
+        case 72: launch_scan8p<16, 512, 8>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
+        case 73: launch_scan8p<24, 512, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
+        default: launch_scan8p<24, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;    // 70
+    }
+}
+
+// the same for 64-bit codes: zero the class counters, count, plan, scatter
+pqkm_status regroup_codes8(const uint8_t* codes, int64_t cnt, uint4* gc8, GroupPlan8* plan, hipStream_t st)
+{
+    const int64_t na = group_alloc(cnt);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(64), dim3(256), 0, st, plan->count, (int64_t)GROUP8_CLASSES);
+    unsigned g = (unsigned)((cnt + 1023) / 1024 < 4096 ? (cnt + 1023) / 1024 : 4096);
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(code8_class_count_kernel, dim3(g), dim3(256), 0, st, codes, cnt, plan);
+    hipLaunchKernelGGL(code8_group_plan_kernel, dim3(1), dim3(1024), 0, st, plan);
+    hipLaunchKernelGGL(code8_group_scatter_kernel, dim3(g), dim3(256), 0, st, codes, cnt, plan, gc8, na);
+    return launched();
 }
 
 // regroup `cnt` codes into gco: three launches on the stream
@@ -239,6 +283,8 @@ void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4
         case 3: launch_scan_skew<8, 12, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 4: launch_scan_skew<8, 16, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 5: launch_scan_skew<8, 24, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 40: launch_scan8p<24, 512, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
+        case 41: launch_scan8p<12, 1024, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
         default: launch_scan_skew<8, 8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
@@ -270,16 +316,25 @@ void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float
 
 // Which scan runs: for M = 4 with the default variant, the regrouped half-plane scan when there is enough work
 // to pay for regrouping (a pass over the codes) and the subspace-skewed scan otherwise.
-inline int effective_variant(int M, int variant, int64_t N, int K)
+inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t* codes)
 {
-    // the half-plane scans address the tile images through one 32-bit buffer offset: below 4 GB of images only
-    const bool img32 = (int64_t)((K + 31) / 32) * TILE_BYTES < (int64_t)0xfff00000;
-    if (M == 4 && !img32 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 34;
+    // the regrouped scans address the tile images through one 32-bit buffer offset: below 4 GB of images only
+    const int TK = 128 / M;
+    const bool img32 = (int64_t)((K + TK - 1) / TK) * TILE_BYTES < (int64_t)0xfff00000;
+    const bool special = (variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79);
+    if (M == 8) {
+        const bool ok8 = img32 && ((uintptr_t)codes & 7) == 0;
+        if (special && !ok8) return 0;
+        // 65536 residue classes: regrouping pays once most classes hold a few dozen codes
+        if (variant == 0 && ok8 && K >= 256 && N >= ((int64_t)1 << 22)) return 70;
+        return variant;
+    }
+    if (M == 4 && !img32 && special) return 34;
     if (M != 4 || variant != 0) return variant;
     if (K < 128 || N < 65536 || !img32) return 34;
     return 70;                            // 32 codes per lane-slot, 512 threads: the fastest measured shape at every size
 }
-inline bool variant_grouped(int M, int variant) { return M == 4 && variant >= 70 && variant <= 79; }
+inline bool variant_grouped(int M, int variant) { return (M == 4 || M == 8) && variant >= 70 && variant <= 79; }
 
 template <int M>
 pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers, int K, const float* tables,
@@ -289,7 +344,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     constexpr int TK = 128 / M;
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
-    const int variant = effective_variant(M, opt.scan_variant, N, K);
+    const int variant = effective_variant(M, opt.scan_variant, N, K, codes);
     const int layout = variant_layout(M, variant);
     if (layout == 2 && M == 4)
         hipLaunchKernelGGL((tile_image_kernel<4, 2>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
@@ -307,11 +362,15 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     const float4* rows = reinterpret_cast<const float4*>(ws + c.rows_off);
     uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
+    uint4* gc8 = reinterpret_cast<uint4*>(ws + c.gc8_off);
+    GroupPlan8* plan8 = reinterpret_cast<GroupPlan8*>(ws + c.plan8_off);
     for (int64_t n0 = 0; n0 < N; n0 += per_launch) {
         int64_t cnt = N - n0 < per_launch ? N - n0 : per_launch;
         // the regrouped copy survives between calls only when one launch covers all codes
         if (grouped && !(reuse_groups && N <= per_launch)) {
-            if (regroup_codes(codes + n0 * M, cnt, gco, plan, st) != PQKM_OK) return PQKM_ERR_DEVICE;
+            const pqkm_status rs = (M == 8) ? regroup_codes8(codes + n0 * M, cnt, gc8, plan8, st)
+                                            : regroup_codes(codes + n0 * M, cnt, gco, plan, st);
+            if (rs != PQKM_OK) return PQKM_ERR_DEVICE;
         }
         EventPair ev{};
         bool prof = false;
@@ -327,7 +386,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             }
         }
         if (prof) hipEventRecord(ev.a, st);
-        if (grouped)
+        if (grouped && M == 8)
+            launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
+                                 assign + n0, dist ? dist + n0 : nullptr, st);
+        else if (grouped)
             launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows,
                                 (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st);
         else
@@ -360,7 +422,7 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
     char* wsc = static_cast<char*>(ws);
     switch (M) {
         case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
-        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
+        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
         case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
         default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
     }

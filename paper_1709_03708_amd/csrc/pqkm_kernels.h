@@ -1036,6 +1036,383 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
+// M = 8 (64-bit codes): regrouping and scan with conflict-free reads, as for M = 4.
+//
+// A tile is 16 centers, img[tile][m][x][16]: plane m at byte m*16384, row x of 64 bytes, so the
+// bank quarter of a slot's read is x mod 4 in each of its 8 reads.  A group of four codes reads
+// conflict-free when their subcodes differ mod 4 in all eight subspaces; the class of a code is
+// now 16 bits (65536 classes), the orbits are again c, c^a, c^b, c^a^b for masks whose 2-bit fields
+// are non-zero and different in every subspace, and the plan is the same greedy matching over a
+// fixed list of mask pairs.  With 65536 classes the per-class counters live in global memory:
+// ranks come from one global atomic per code (spread over 65536 addresses), so the order inside
+// a class is not fixed from run to run -- the results are, since the scan treats every code alone.
+// The scan needs no skew steps: 8 reads and 28 adds per 4 evaluations where the skewed scan below
+// has 11 and 40.
+// ---------------------------------------------------------------------------------------------
+constexpr int GROUP8_CLASSES = 65536;
+constexpr int GROUP8_ORBITS = GROUP8_CLASSES / 4;
+
+__constant__ uint16_t group8_masks[GROUP_ROUNDS][2] = {
+    {0x6b55, 0xd6ee}, {0x76e5, 0xd99f}, {0xb7eb, 0x5a96}, {0xfa6e, 0xa5b7}, {0x6b66, 0xdefd}, {0xe76b, 0xbad6},
+    {0x5ebb, 0xb9ee}, {0xa69a, 0x7d67}, {0x6afe, 0xdfab}, {0x799d, 0x9ffa}, {0x97f7, 0x6e69}, {0x9d7d, 0xf6eb},
+    {0xbf66, 0xe9f9}, {0xd5ad, 0xbbfb}, {0xdd95, 0xa6fa}, {0x9f59, 0x69ff}};
+
+struct GroupPlan8 {
+    uint32_t count[GROUP8_CLASSES];                       // codes per class
+    uint32_t cursor[GROUP8_CLASSES];                      // codes handed out so far (scatter pass)
+    uint32_t rem[GROUP_ROUNDS + 1][GROUP8_CLASSES];       // [d][class]: codes of the class not matched before round d; [last] = left over
+    uint32_t gbase[GROUP_ROUNDS][GROUP8_CLASSES];         // [d][class]: index of the first group the class's orbit forms in round d
+    uint32_t lbase[GROUP8_CLASSES];                       // index of the class's first left-over code among all left-overs
+    uint32_t groups, leftovers, lgroups, period_m1;
+};
+
+__device__ __forceinline__ uint32_t code8_class(uint32_t lo, uint32_t hi)
+{
+    return code_class(lo) | (code_class(hi) << 8);
+}
+
+__global__ __launch_bounds__(256) void code8_class_count_kernel(const uint8_t* __restrict__ codes, int64_t n,
+                                                                GroupPlan8* __restrict__ plan)
+{
+    const uint2* cw = reinterpret_cast<const uint2*>(codes);
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n; i += stride) {
+        const uint2 v = cw[i];
+        atomicAdd(&plan->count[code8_class(v.x, v.y)], 1u);
+    }
+}
+
+// one workgroup of 1024 threads: thread t owns the orbits t, t + 1024, ... of every round (an orbit is named by its
+// class with residue 0 in subspace 0, class = 4 * orbit index; groups are numbered in orbit order).  The tables
+// are stored round-major so that the 64 lanes of a wave touch one kilobyte per access.
+__global__ __launch_bounds__(1024) void code8_group_plan_kernel(GroupPlan8* __restrict__ plan)
+{
+    constexpr int OPT = GROUP8_ORBITS / 1024;      // orbits per thread
+    __shared__ uint32_t wsum[OPT][16];             // per stripe of 1024 orbits and wave: groups formed
+    __shared__ uint32_t sbase[OPT];                // per stripe: groups formed by the stripes before it
+    __shared__ uint32_t round_total;
+    const int tid = threadIdx.x, wv = tid >> 6;
+    for (int c = tid; c < GROUP8_CLASSES; c += 1024) {
+        plan->rem[0][c] = plan->count[c];
+        plan->cursor[c] = 0u;
+    }
+    __syncthreads();
+    uint32_t gtot = 0;
+    for (int d = 0; d < GROUP_ROUNDS; ++d) {
+        const uint32_t a = group8_masks[d][0], b = group8_masks[d][1];
+        uint32_t m[OPT], r0[OPT], r1[OPT], r2[OPT], r3[OPT], inc[OPT];
+#pragma unroll
+        for (int i = 0; i < OPT; ++i) {
+            const uint32_t c0 = (uint32_t)(i * 1024 + tid) << 2;
+            // values written by other threads of this workgroup in the previous round: read past the L1
+            r0[i] = __hip_atomic_load(&plan->rem[d][c0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1[i] = __hip_atomic_load(&plan->rem[d][c0 ^ a], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r2[i] = __hip_atomic_load(&plan->rem[d][c0 ^ b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r3[i] = __hip_atomic_load(&plan->rem[d][c0 ^ a ^ b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int i = 0; i < OPT; ++i) {
+            uint32_t v = r0[i] < r1[i] ? r0[i] : r1[i];
+            v = v < r2[i] ? v : r2[i];
+            v = v < r3[i] ? v : r3[i];
+            m[i] = v;
+            inc[i] = wave_inclusive_scan(v);
+            if ((tid & 63) == 63) wsum[i][wv] = inc[i];
+        }
+        __syncthreads();
+        if (tid < OPT) {
+            // exclusive prefix of the stripe totals: thread i sums the stripes before stripe i
+            uint32_t e = 0;
+            for (int ii = 0; ii < tid; ++ii)
+                for (int w = 0; w < 16; ++w) e += wsum[ii][w];
+            sbase[tid] = e;
+            if (tid == OPT - 1) {
+                uint32_t t = e;
+                for (int w = 0; w < 16; ++w) t += wsum[OPT - 1][w];
+                round_total = t;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < OPT; ++i) {
+            uint32_t before = gtot + sbase[i] + inc[i] - m[i];
+            for (int w = 0; w < wv; ++w) before += wsum[i][w];
+            const uint32_t c0 = (uint32_t)(i * 1024 + tid) << 2, c1 = c0 ^ a, c2 = c0 ^ b, c3 = c0 ^ a ^ b;
+            plan->gbase[d][c0] = before;
+            plan->gbase[d][c1] = before;
+            plan->gbase[d][c2] = before;
+            plan->gbase[d][c3] = before;
+            plan->rem[d + 1][c0] = r0[i] - m[i];
+            plan->rem[d + 1][c1] = r1[i] - m[i];
+            plan->rem[d + 1][c2] = r2[i] - m[i];
+            plan->rem[d + 1][c3] = r3[i] - m[i];
+        }
+        gtot += round_total;
+        __syncthreads();               // rem[d+1] complete; wsum, sbase, round_total free for the next round
+    }
+    // left-overs: exclusive prefix over classes in ascending order, thread t owns classes 64t .. 64t+63
+    {
+        constexpr int CPT = GROUP8_CLASSES / 1024;
+        uint32_t mine = 0;
+        for (int i = 0; i < CPT; ++i)
+            mine += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][tid * CPT + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t inc = wave_inclusive_scan(mine);
+        if ((tid & 63) == 63) wsum[0][wv] = inc;
+        __syncthreads();
+        uint32_t e = inc - mine;
+        for (int w = 0; w < wv; ++w) e += wsum[0][w];
+        for (int i = 0; i < CPT; ++i) {
+            plan->lbase[tid * CPT + i] = e;
+            e += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][tid * CPT + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (tid == 1023) {
+            const uint32_t ltot = e, lg = (ltot + 3u) / 4u;
+            plan->groups = gtot;
+            plan->leftovers = ltot;
+            plan->lgroups = lg;
+            plan->period_m1 = (lg > 0 && gtot >= lg) ? gtot / lg : 0u;
+        }
+    }
+}
+
+// gc8[pos] = (code low word, code high word, original index, 0); positions that receive no code get ORIGIN_NONE
+__global__ __launch_bounds__(256) void code8_group_scatter_kernel(const uint8_t* __restrict__ codes, int64_t n,
+                                                                  GroupPlan8* __restrict__ plan,
+                                                                  uint4* __restrict__ gc8, int64_t n_alloc)
+{
+    const uint2* cw = reinterpret_cast<const uint2*>(codes);
+    const uint32_t gtot = plan->groups, ltot = plan->leftovers, lg = plan->lgroups, dm1 = plan->period_m1;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (; i < n; i += stride) {
+        const uint2 v = cw[i];
+        const uint32_t c = code8_class(v.x, v.y);
+        const uint32_t rank = atomicAdd(&plan->cursor[c], 1u);
+        const uint32_t tot = plan->rem[0][c];
+        const uint32_t left = plan->rem[GROUP_ROUNDS][c];
+        int64_t u;
+        uint32_t slot;
+        if (rank < tot - left) {
+            // round d took the ranks [tot - rem[d], tot - rem[d+1]): largest d with tot - rem[d] <= rank
+            int d = 0;
+#pragma unroll
+            for (int step = GROUP_ROUNDS / 2; step >= 1; step >>= 1)
+                if (rank >= tot - plan->rem[d + step][c]) d += step;
+            const uint32_t g = plan->gbase[d][c] + (rank - (tot - plan->rem[d][c]));
+            slot = c & 3u;
+            uint32_t before = dm1 ? g / dm1 : 0u;
+            if (before > lg) before = lg;
+            u = (int64_t)g + before;
+        } else {
+            const uint32_t li = plan->lbase[c] + (rank - (tot - left));
+            const uint32_t jg = li % lg;
+            slot = li / lg;
+            u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+        }
+        const int64_t pos = group_slot_position(u, slot);
+        if (pos < n_alloc) gc8[pos] = make_uint4(v.x, v.y, (uint32_t)i, 0u);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 32) {
+        const int tid = threadIdx.x;
+        const int64_t T = (int64_t)gtot + lg;
+        int64_t pos = -1;
+        if (tid < 4) {
+            const uint32_t li = ltot + (uint32_t)tid;
+            if (li < 4u * lg) {
+                const uint32_t jg = li % lg;
+                const int64_t ul = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+                pos = group_slot_position(ul, li / lg);
+            }
+        } else if (tid < 8) {
+            if (T & 1) pos = group_slot_position(T, (uint32_t)tid - 4);
+        } else {
+            pos = ((T + 1) >> 1) * 8 + (tid - 8);
+        }
+        if (pos >= 0 && pos < n_alloc) gc8[pos] = make_uint4(0u, 0u, ORIGIN_NONE, 0u);
+    }
+}
+
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                const uint4* __restrict__ gc8,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist)
+{
+    constexpr int LPS = 4, TK = 16, M = 8;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr uint32_t PLANE = 16384;       // bytes per subspace plane: 256 subcodes x 16 centers
+    static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+    static_assert(R % 4 == 0 && R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid % LPS;
+    const int c = tid / LPS;
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t four = 4;
+
+    // per code four registers of 16-bit fields (x_m*64 + 16q)/16, the planes of m >= 4 addressed from 64 KB up so
+    // that every remaining plane offset fits the DS immediate
+    uint32_t fld[R][4];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        uint32_t lo, hi;
+        if (gc8) {
+            const uint4 g = gc8[n];
+            lo = g.x;
+            hi = g.y;
+        } else {
+            const uint2 g = *reinterpret_cast<const uint2*>(codes + n * 8);
+            lo = g.x;
+            hi = g.y;
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t src = w < 2 ? lo : hi;
+            const uint32_t xa = (src >> (16 * (w & 1))) & 255u, xb = (src >> (16 * (w & 1) + 8)) & 255u;
+            const uint32_t up = w < 2 ? 0u : 4096u;
+            fld[r][w] = (((xa << 2) | (uint32_t)q) + up) | ((((xb << 2) | (uint32_t)q) + up) << 16);
+        }
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    auto issue = [&](int step) -> float4 {
+        const int r = step / M, m = step % M;
+        const uint32_t ad = (m & 1) ? sdwa_shl_word1(four, fld[r][m / 2]) : sdwa_shl_word0(four, fld[r][m / 2]);
+        return lds_read16(tb, ad + (uint32_t)(m & 3) * PLANE);
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        float4 ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+        float4 sa;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int step = M * r + m;
+                const float4 cur = ring[step % DEPTH];
+                if (step + DEPTH < M * R) ring[step % DEPTH] = issue(step + DEPTH);
+                if (m == 0) {
+                    sa = cur;
+                } else {
+                    sa.x = sa.x + cur.x; sa.y = sa.y + cur.y; sa.z = sa.z + cur.z; sa.w = sa.w + cur.w;
+                }
+                if (m == M - 1) {
+                    const float m4 = min3_f32(sa.x, sa.y, sa.z);
+                    const float nb = min3_f32(m4, sa.w, best[r]);
+                    tix[r] = (nb < best[r]) ? t : tix[r];
+                    best[r] = nb;
+                }
+            }
+        }
+    }
+
+    // Epilogue, transposed through LDS as in assign_scan4p_kernel: lane l finishes the codes l, l + THREADS, ...
+    constexpr int CPL = R / 4;
+    __syncthreads();
+    {
+        float2* rec = reinterpret_cast<float2*>(tile);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            rec[(r * SLOTS + c) * 4 + q] = make_float2(best[r], __builtin_bit_cast(float, tix[r]));
+    }
+    __syncthreads();
+    __amdgpu_buffer_rsrc_t rs_img = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(img), 0, (uint32_t)ntiles * (uint32_t)TILE_BYTES, 0x00020000);
+    constexpr int TNONE = 0x7fffffff;
+#pragma unroll 1
+    for (int i0 = 0; i0 < CPL; ++i0) {
+        const int j = i0 * THREADS + tid;
+        int64_t n = base + j;
+        const bool live = n < N;
+        if (!live) n = N - 1;
+        const float4 ra = lds_read16(tb, (uint32_t)j * 32u), rb = lds_read16(tb, (uint32_t)j * 32u + 16u);
+        const float b0 = ra.x, b1 = ra.z, b2 = rb.x, b3 = rb.z;
+        const int t0 = __builtin_bit_cast(int, ra.y), t1 = __builtin_bit_cast(int, ra.w);
+        const int t2 = __builtin_bit_cast(int, rb.y), t3 = __builtin_bit_cast(int, rb.w);
+        const float sm = __builtin_fminf(__builtin_fminf(b0, b1), __builtin_fminf(b2, b3));
+        const int c0 = (b0 == sm && t0 >= 0) ? t0 : TNONE, c1 = (b1 == sm && t1 >= 0) ? t1 : TNONE;
+        const int c2 = (b2 == sm && t2 >= 0) ? t2 : TNONE, c3 = (b3 == sm && t3 >= 0) ? t3 : TNONE;
+        int tm = c0 < c1 ? c0 : c1;
+        tm = tm < c2 ? tm : c2;
+        tm = tm < c3 ? tm : c3;
+        uint32_t cand = (uint32_t)(c0 == tm) | ((uint32_t)(c1 == tm) << 1) | ((uint32_t)(c2 == tm) << 2) |
+                        ((uint32_t)(c3 == tm) << 3);
+        if (tm == TNONE || !live) cand = 0u;
+        uint32_t lo, hi, og;
+        if (gc8) {
+            const uint4 g = gc8[n];
+            lo = g.x;
+            hi = g.y;
+            og = live ? g.z : ORIGIN_NONE;
+        } else {
+            const uint2 g = *reinterpret_cast<const uint2*>(codes + n * 8);
+            lo = g.x;
+            hi = g.y;
+            og = live ? 0u : ORIGIN_NONE;
+        }
+        int bi = IDX_NONE;
+        while (__any(cand != 0u)) {                 // one trip unless lane positions tie exactly
+            const int qe = cand ? (int)__builtin_ctz(cand) : 0;
+            const uint32_t tb0 = cand ? (uint32_t)tm * (uint32_t)TILE_BYTES + (uint32_t)qe * 16u : 0xfff00000u;
+            v4f sv = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, tb0 + ((lo & 255u) << 6), 0, 0));
+#pragma unroll
+            for (int m = 1; m < M; ++m) {
+                const uint32_t x = ((m < 4 ? lo : hi) >> (8 * (m & 3))) & 255u;
+                sv = sv + __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, tb0 + (x << 6), m * PLANE, 0));
+            }
+            if (cand) {
+                const int kb = tm * TK + qe * 4;
+                int k = IDX_NONE;
+                if (sv.w == sm) k = kb + 3;
+                if (sv.z == sm) k = kb + 2;
+                if (sv.y == sm) k = kb + 1;
+                if (sv.x == sm) k = kb;
+                bi = k < bi ? k : bi;
+                cand &= cand - 1u;
+            }
+        }
+        if (og != ORIGIN_NONE) {
+            const int64_t dst = gc8 ? (int64_t)og : base + j;
+            assign[dst] = (bi == IDX_NONE) ? 0 : bi;
+            if (dist) dist[dst] = sm;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Subspace-skewed scan for M = 8, 16, 32 (64-bit SIFT-like codes, CNN-feature codes; Sec. 4).
 //
 // All M subspaces of TK = 128/M centers are resident (x-major image: row (x, m) of TK*4 bytes at

@@ -132,6 +132,37 @@ def test_assign_regrouped_scan(env, variant, kind, N):
         _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
 
 
+@pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73])
+@pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 300007), ("uniform", 4093), ("uniform", 3),
+                                    ("one_class", 5000), ("latin", 8192)])
+def test_assign_regrouped_scan_64bit_codes(env, variant, kind, N):
+    """M = 8 scan over regrouped codes (65536 residue classes, ranks from global atomics): regrouping must not
+    change any result, whatever the class mix."""
+    W = env["W"]
+    rng = np.random.default_rng(N + variant)
+    w = workload(3, N=max(N, 300), K=141, T=60)
+    allc = W.codes_numpy(w)
+    centers = allc[W.init_center_indices(w)].copy()
+    if kind == "templates":
+        codes = allc[:N]
+    else:
+        codes = rng.integers(0, 256, size=(N, 8), dtype=np.uint8)
+        if kind == "one_class":
+            codes &= 0xFC
+        elif kind == "latin":
+            lat = np.stack([rng.permuted(np.tile(np.arange(4, dtype=np.uint8), (N // 4, 1)), axis=1)
+                            for _ in range(8)], axis=2).reshape(-1, 8)
+            codes = (codes & 0xFC) | lat
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+    if variant == 70:
+        ham = np.ones((8, 256, 256), np.float32)
+        for m in range(8):
+            np.fill_diagonal(ham[m], 0)
+        _check_assign(env, (codes % 3).astype(np.uint8), (centers % 3).astype(np.uint8), ham, assign_kernel=2,
+                      scan_variant=variant)
+
+
 def test_regrouped_scan_in_several_launches(env):
     """Scan launches smaller than N: every launch regroups its own stretch of the codes, and pqkm_fit cannot keep
     the regrouped copy between iterations (it holds one launch only)."""
