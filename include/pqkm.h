@@ -156,7 +156,9 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
  *                        scan), 1..99 = one specific compiled scan and launch shape (for tuning sweeps;
  *                        e.g. 34 = the skewed M = 4 scan without regrouping, 70 = the regrouped one)
  *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
- *                        per code and subspace, 2 = force the LDS-privatised histogram
+ *                        per code and subspace, 2 = force the LDS-privatised histogram over cluster
+ *                        groups (falls back when K needs more than 255 groups), 3 = force the
+ *                        histogram over code indices sorted by cluster
  *   "hist_groups"        target number of cluster groups of the LDS-privatised histogram,
  *                        1..255 (default 64); changes pqkm_workspace_bytes, so set it before
  *                        sizing the workspace

@@ -18,7 +18,7 @@ using namespace pqkm;
 struct Options {
     int assign_kernel = 0;   // 0 auto, 1 generic, 2 tiled
     int scan_variant = 0;    // 0 auto, else a specific instantiation (tuning)
-    int hist_kernel = 0;     // 0 auto, 1 global atomics, 2 LDS-privatised owner path
+    int hist_kernel = 0;     // 0 auto, 1 global atomics, 2 LDS-privatised owner path, 3 sorted by cluster
     int profile = 0;         // bracket scan kernels with events
     int64_t launch_codes = (int64_t)1 << 26;   // codes per scan launch
 };
@@ -35,7 +35,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, total;
+        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -95,6 +95,14 @@ Carve carve(int64_t N, int M, int K)
         off += align256((size_t)na * sizeof(uint2));
         c.plan_off = off;
         off += align256(sizeof(GroupPlan));
+    }
+    // sorted-path histogram: code indices sorted by cluster (u32), cluster sizes, starts and cursors
+    c.sidx_off = c.seg_off = off;
+    if (N <= (int64_t)0xffffffff) {
+        c.sidx_off = off;
+        off += align256((size_t)N * sizeof(uint32_t));
+        c.seg_off = off;
+        off += 3 * align256(((size_t)K + 1) * sizeof(uint32_t));
     }
     c.gc8_off = c.plan8_off = off;
     if (M == 8) {
@@ -447,7 +455,7 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
         std::lock_guard<std::mutex> lk(g_mu);
         force = g_opt.hist_kernel;
     }
-    const bool owner = hp.KT >= 1 && hp.groups <= 255 && force != 1 && (force == 2 || hp.cheap);
+    const bool owner = hp.KT >= 1 && hp.groups <= 255 && force != 1 && force != 3 && (force == 2 || hp.cheap);
     int S = 1;
     size_t part_stride = 0;
     uint32_t* parts = hist;
@@ -467,6 +475,24 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
         else
             hipLaunchKernelGGL((histogram_owner_kernel<HIST_LDS_WORDS>), dim3((unsigned)(hp.groups * S)), dim3(1024),
                                0, st, codes, N, M, assign, gid, K, hp.KT, S, parts, part_stride);
+    } else if (force != 1 && N <= (int64_t)0xffffffff && N > 0 && M <= 128) {
+        // sorted path: counting sort of the code indices by cluster, then LDS histograms per stretch of clusters
+        const size_t seg_stride = align256(((size_t)K + 1) * sizeof(uint32_t));
+        uint32_t* sidx = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.sidx_off);
+        uint32_t* cnt = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off);
+        uint32_t* start = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off + seg_stride);
+        uint32_t* cursor = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off + 2 * seg_stride);
+        unsigned zb = (unsigned)((K + 255) / 256 < 1024 ? (K + 255) / 256 : 1024);
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, cnt, (int64_t)K);
+        unsigned cb = (unsigned)((N + 4095) / 4096 < 1024 ? (N + 4095) / 4096 : 1024);
+        hipLaunchKernelGGL(seg_count_kernel, dim3(cb), dim3(1024), 0, st, assign, N, K, cnt);
+        hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, K, start, cursor);
+        unsigned sb = (unsigned)((N + 1023) / 1024 < 8192 ? (N + 1023) / 1024 : 8192);
+        hipLaunchKernelGGL(seg_scatter_kernel, dim3(sb), dim3(256), 0, st, assign, N, K, start, cursor, sidx);
+        int KT = (HIST_LDS_WORDS / L) / M;
+        if (KT > 128) KT = 128;
+        hipLaunchKernelGGL(seg_hist_kernel, dim3((unsigned)((K + KT - 1) / KT)), dim3(1024), 0, st, codes, M, start, sidx,
+                           K, KT, hist);
     } else {
         zero_hist();
         const int64_t per = (int64_t)1 << 30;
@@ -647,7 +673,7 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
         if (value < 0 || value > 99) return PQKM_ERR_SHAPE;
         g_opt.scan_variant = value;
     } else if (strcmp(name, "hist_kernel") == 0) {
-        if (value < 0 || value > 2) return PQKM_ERR_SHAPE;
+        if (value < 0 || value > 3) return PQKM_ERR_SHAPE;
         g_opt.hist_kernel = value;
     } else if (strcmp(name, "hist_groups") == 0) {
         if (value < 1 || value > 255) return PQKM_ERR_SHAPE;

@@ -1616,6 +1616,117 @@ __global__ __launch_bounds__(256) void histogram_atomic_kernel(const uint8_t* __
 }
 
 // ---------------------------------------------------------------------------------------------
+// Eq. 7, sorted path (many centers): the code indices are first sorted by cluster with a counting
+// sort (cluster sizes, exclusive prefix, scatter: one global atomic per code instead of one per
+// code and subspace), then a workgroup owns KT consecutive clusters, reads their codes from the
+// contiguous stretch of the sorted index array and counts into LDS; the private histograms are
+// the result (written whole: no clearing pass, no global atomics on bins).  Out-of-range
+// assignments are dropped by the sort.  The order of the indices inside a cluster depends on the
+// atomics; counts do not.
+// ---------------------------------------------------------------------------------------------
+constexpr int SEG_COUNT_LDS_K = 16384;      // cluster sizes are counted in LDS up to this many clusters
+
+__global__ __launch_bounds__(1024) void seg_count_kernel(const int32_t* __restrict__ assign, int64_t N, int K,
+                                                         uint32_t* __restrict__ cnt)
+{
+    __shared__ uint32_t h[SEG_COUNT_LDS_K];
+    const bool lds = K <= SEG_COUNT_LDS_K;
+    if (lds) {
+        for (int k = threadIdx.x; k < K; k += 1024) h[k] = 0u;
+        __syncthreads();
+    }
+    for (int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 1024) {
+        const int k = assign[i];
+        if ((unsigned)k < (unsigned)K) atomicAdd(lds ? &h[k] : &cnt[k], 1u);
+    }
+    if (lds) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += 1024)
+            if (h[k]) atomicAdd(&cnt[k], h[k]);
+    }
+}
+
+// one workgroup: start[0..K] = exclusive prefix of cnt, cursor[0..K) = 0
+__global__ __launch_bounds__(1024) void seg_prefix_kernel(const uint32_t* __restrict__ cnt, int K,
+                                                          uint32_t* __restrict__ start, uint32_t* __restrict__ cursor)
+{
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0u;
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += 1024) {
+        const int k = k0 + tid;
+        const uint32_t v = k < K ? cnt[k] : 0u;
+        const uint32_t inc = wave_inclusive_scan(v);
+        if ((tid & 63) == 63) wsum[tid >> 6] = inc;
+        __syncthreads();
+        uint32_t e = carry + inc - v;
+        for (int w = 0; w < (tid >> 6); ++w) e += wsum[w];
+        if (k < K) {
+            start[k] = e;
+            cursor[k] = 0u;
+        }
+        __syncthreads();
+        if (tid == 1023) carry = e + v;
+        __syncthreads();
+    }
+    if (tid == 0) start[K] = carry;
+}
+
+__global__ __launch_bounds__(256) void seg_scatter_kernel(const int32_t* __restrict__ assign, int64_t N, int K,
+                                                          const uint32_t* __restrict__ start,
+                                                          uint32_t* __restrict__ cursor, uint32_t* __restrict__ sidx)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
+        const int k = assign[i];
+        if ((unsigned)k < (unsigned)K) sidx[start[k] + atomicAdd(&cursor[k], 1u)] = (uint32_t)i;
+    }
+}
+
+// workgroup b owns clusters b*KT .. b*KT+KT-1; LDS holds KT*M*256 counters (at most HIST_LDS_WORDS)
+__global__ __launch_bounds__(1024) void seg_hist_kernel(const uint8_t* __restrict__ codes, int M,
+                                                        const uint32_t* __restrict__ start,
+                                                        const uint32_t* __restrict__ sidx, int K, int KT,
+                                                        uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t lh[32768];
+    __shared__ uint32_t st[130];
+    const int tid = threadIdx.x;
+    const int k0 = blockIdx.x * KT;
+    const int nk = K - k0 < KT ? K - k0 : KT;
+    const int words = nk * M * L;
+    for (int i = tid; i < words; i += 1024) lh[i] = 0u;
+    for (int i = tid; i <= nk; i += 1024) st[i] = start[k0 + i];
+    __syncthreads();
+    const uint32_t p0 = st[0], p1 = st[nk];
+    const bool wordwise = (M & 3) == 0 && ((uintptr_t)codes & 3) == 0;
+    for (uint32_t p = p0 + tid; p < p1; p += 1024) {
+        // the cluster of position p: the last kk with st[kk] <= p
+        int kk = 0;
+        for (int step = 64; step >= 1; step >>= 1)
+            if (kk + step < nk && st[kk + step] <= p) kk += step;
+        const uint8_t* x = codes + (size_t)sidx[p] * M;
+        uint32_t* h = lh + kk * M * L;
+        if (wordwise) {
+            const uint32_t* xw = reinterpret_cast<const uint32_t*>(x);
+            for (int w = 0; w < M / 4; ++w) {
+                const uint32_t v = xw[w];
+                atomicAdd(&h[(4 * w + 0) * L + (v & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 1) * L + ((v >> 8) & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 2) * L + ((v >> 16) & 255u)], 1u);
+                atomicAdd(&h[(4 * w + 3) * L + (v >> 24)], 1u);
+            }
+        } else {
+            for (int m = 0; m < M; ++m) atomicAdd(&h[m * L + x[m]], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* out = hist + (size_t)k0 * M * L;
+    for (int i = tid; i < words; i += 1024) out[i] = lh[i];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Eq. 7, owner path: LDS-privatised histograms, no global atomics.
 //
 // Clusters are grouped KT at a time, KT chosen so that there are up to 255 groups (about one

@@ -240,8 +240,9 @@ def test_assign_degenerate_inputs(env):
 
 
 # ------------------------------------------------------------------------------------ update
-@pytest.mark.parametrize("hist_kernel", [0, 1, 2])
-@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000), (4, 70, 300_000)])
+@pytest.mark.parametrize("hist_kernel", [0, 1, 2, 3])
+@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000), (4, 70, 300_000),
+                                   (8, 20_000, 200_000), (4, 1000, 50_000)])
 def test_update_matches_oracle(env, M, K, N, hist_kernel):
     rng = np.random.default_rng(M * K)
     pq, oracle = env["pq"], env["oracle"]
