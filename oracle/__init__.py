@@ -6,7 +6,7 @@ leg may import this package; the product path never does, and this package
 imports nothing from the HIP side.
 
 Function names follow the paper: tables (Sec. 2.2), assign (Eq. 5),
-histogram (Eq. 7), vote (Eq. 8), update_naive (Eq. 6), fit (Alg. 1).
+histogram (Eq. 7), vote (Eq. 8), update_naive (Eq. 6), fit (Alg. 1), encode / decode (Sec. 2.2).
 """
 from __future__ import annotations
 
@@ -54,6 +54,10 @@ def _load():
         lib.pqko_fit.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp]
         lib.pqko_fit_until.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp]
         lib.pqko_fit_until.restype = ctypes.c_int
+        lib.pqko_encode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        lib.pqko_encode.restype = None
+        lib.pqko_decode_f32.argtypes = [vp, i32, i32, vp, i64, vp]
+        lib.pqko_decode_f32.restype = None
         for name in ("pqko_set_threads", "pqko_build_tables", "pqko_decode", "pqko_sdc_pairs",
                      "pqko_assign", "pqko_histogram", "pqko_vote", "pqko_update",
                      "pqko_update_naive", "pqko_fit"):
@@ -100,6 +104,32 @@ def decode(codewords, codes) -> np.ndarray:
     assert codes.shape == (N, M)
     out = np.empty((N, M * Ds), dtype=np.float64)
     _load().pqko_decode(_p(cw), M, Ds, _p(codes), N, _p(out))
+    return out
+
+
+def encode(vectors, codewords, want_dist: bool = False):
+    """Sec. 2.2: vectors [N][M*Ds] f32 -> codes [N][M] u8 (and the squared distances [N][M] f32)."""
+    cw = _chk(codewords, np.float32)
+    M, l, Ds = cw.shape
+    assert l == L
+    v = _chk(vectors, np.float32)
+    N = v.shape[0]
+    assert v.shape == (N, M * Ds)
+    codes = np.empty((N, M), dtype=np.uint8)
+    d2 = np.empty((N, M), dtype=np.float32) if want_dist else None
+    _load().pqko_encode(_p(v), N, M, Ds, _p(cw), _p(codes), _p(d2))
+    return (codes, d2) if want_dist else codes
+
+
+def decode_f32(codewords, codes) -> np.ndarray:
+    """codes [N][M] u8 -> reconstructed vectors [N][M*Ds] f32 (the codewords themselves)."""
+    cw = _chk(codewords, np.float32)
+    M, _, Ds = cw.shape
+    codes = _chk(codes, np.uint8)
+    N = codes.shape[0]
+    assert codes.shape == (N, M)
+    out = np.empty((N, M * Ds), dtype=np.float32)
+    _load().pqko_decode_f32(_p(cw), M, Ds, _p(codes), N, _p(out))
     return out
 
 

@@ -18,6 +18,7 @@
  *   - hist:    Eq. 7   (L-bin frequency histogram of a cluster's subcodes)
  *   - vote:    Eq. 8   (argmin over l of v = A^m h, zero bins skipped)
  *   - fit:     Alg. 1  (linear-scan branch: repeat { assign ; update })
+ *   - encode:  Sec. 2.2 (per subvector, the index of the closest codeword)
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   indices are 0..255 instead of 1..L; ties in either argmin go to the
@@ -25,7 +26,10 @@
  *   used everywhere on the path; table entries are fp32, the SDC running sum
  *   is fp32 added in ascending m with no fused operation; the vote
  *   accumulates v in fp32 with one explicit fused multiply-add per non-zero
- *   bin in ascending bin order.
+ *   bin in ascending bin order.  The encoder measures "closest" by the
+ *   squared distance accumulated in fp32 over ascending dimension, one fp32
+ *   subtraction and one fused multiply-add per dimension, and takes the
+ *   lowest index on ties.
  *
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fopenmp -shared -fPIC
  *        (no -ffast-math, no -march flags: arithmetic must be plain IEEE).
@@ -98,6 +102,47 @@ void pqko_decode(const float *codewords, int M, int Ds, const uint8_t *codes, in
         for (int m = 0; m < M; ++m) {
             const float *c = codewords + ((size_t)m * PQKO_L + codes[n * M + m]) * Ds;
             for (int d = 0; d < Ds; ++d) out[((size_t)n * M + m) * Ds + d] = (double)c[d];
+        }
+}
+
+/*
+ * Sec. 2.2 (encoding): each of the M subvectors of a vector is replaced by the
+ * index of its closest codeword.  vectors: [N][M*Ds] fp32, codes: [N][M] u8.
+ * dist2 (may be NULL): [N][M] fp32, the squared distance to the chosen codeword.
+ */
+void pqko_encode(const float *vectors, int64_t N, int M, int Ds, const float *codewords, uint8_t *codes,
+                 float *dist2)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            const float *x = vectors + ((size_t)n * M + m) * Ds;
+            float best = INFINITY;
+            int bl = 0;
+            for (int l = 0; l < PQKO_L; ++l) {
+                const float *c = codewords + ((size_t)m * PQKO_L + l) * Ds;
+                float acc = 0.0f;
+                for (int d = 0; d < Ds; ++d) {
+                    float t = x[d] - c[d];
+                    acc = fmaf(t, t, acc);
+                }
+                if (acc < best) {
+                    best = acc;
+                    bl = l;
+                }
+            }
+            codes[n * M + m] = (uint8_t)bl;
+            if (dist2) dist2[n * M + m] = best;
+        }
+}
+
+/* Sec. 2.2 (reconstructability) in the codewords' own precision: out [N][M*Ds] fp32. */
+void pqko_decode_f32(const float *codewords, int M, int Ds, const uint8_t *codes, int64_t N, float *out)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            const float *c = codewords + ((size_t)m * PQKO_L + codes[n * M + m]) * Ds;
+            for (int d = 0; d < Ds; ++d) out[((size_t)n * M + m) * Ds + d] = c[d];
         }
 }
 

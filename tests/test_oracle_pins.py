@@ -461,3 +461,93 @@ def test_fit_until_stops_at_the_fixed_point_and_reports_statistics(small_problem
     # the cap is honoured
     _, _, _, _, s2 = oracle.fit_until(codes, tables, centers, 2)
     assert len(s2) == 2 and (s2 == stats[:2]).all()
+
+
+# ------------------------------------------------------------------------------------ encode / decode (Sec. 2.2)
+def test_encode_is_nearest_codeword_exact_on_integer_data():
+    """Integer coordinates: every difference, square and partial sum is an exactly representable integer, so the
+    fp32 accumulation equals exact integer arithmetic and the result must equal numpy's integer argmin (first
+    minimum = lowest index) bit for bit, whatever the summation order.  Non-square M*Ds layout catches a
+    transposed subvector split."""
+    rng = np.random.default_rng(21)
+    M, Ds, N = 3, 5, 400
+    cw = rng.integers(-20, 21, size=(M, 256, Ds)).astype(np.float32)
+    v = rng.integers(-25, 26, size=(N, M * Ds)).astype(np.float32)
+    codes, d2 = oracle.encode(v, cw, want_dist=True)
+    vi, ci = v.astype(np.int64).reshape(N, M, Ds), cw.astype(np.int64)
+    for m in range(M):
+        dist = ((vi[:, m, None, :] - ci[m][None, :, :]) ** 2).sum(-1)          # [N][256] exact
+        np.testing.assert_array_equal(codes[:, m], dist.argmin(1))
+        np.testing.assert_array_equal(d2[:, m].astype(np.int64), dist.min(1))
+
+
+def test_encode_scalar_quantiser_closed_form():
+    """Ds = 1 is a scalar quantiser: the closest codeword of x is found by bisection in the sorted codewords."""
+    rng = np.random.default_rng(22)
+    grid = np.sort(rng.choice(np.arange(-4000, 4000), size=256, replace=False)).astype(np.float32)
+    perm = rng.permutation(256)
+    cw = grid[perm].reshape(1, 256, 1)
+    x = (rng.integers(-5000, 5000, size=3000) + 0.25).astype(np.float32)          # never half-way between two codewords
+    codes = oracle.encode(x.reshape(-1, 1), cw)[:, 0]
+    pos = np.searchsorted(grid, x)
+    lo, hi = np.clip(pos - 1, 0, 255), np.clip(pos, 0, 255)
+    nearest = np.where(np.abs(x - grid[lo]) <= np.abs(grid[hi] - x), lo, hi)
+    inv = np.empty(256, np.int64)
+    inv[perm] = np.arange(256)                                                     # sorted position -> codeword index
+    np.testing.assert_array_equal(codes, inv[nearest])
+
+
+def test_encode_real_data_is_optimal_in_exact_arithmetic():
+    """Real-valued data: the chosen codeword's exact (fp64) squared distance is within fp32 rounding of the
+    exact optimum, and the reported distance equals it to fp32 accuracy."""
+    rng = np.random.default_rng(23)
+    M, Ds, N = 4, 32, 300
+    cw = rng.normal(size=(M, 256, Ds)).astype(np.float32)
+    v = rng.normal(size=(N, M * Ds)).astype(np.float32)
+    codes, d2 = oracle.encode(v, cw, want_dist=True)
+    v64, c64 = v.astype(np.float64).reshape(N, M, Ds), cw.astype(np.float64)
+    for m in range(M):
+        dist = ((v64[:, m, None, :] - c64[m][None, :, :]) ** 2).sum(-1)
+        chosen = dist[np.arange(N), codes[:, m]]
+        assert (chosen <= dist.min(1) * (1 + 1e-5)).all()
+        np.testing.assert_allclose(d2[:, m], chosen, rtol=1e-5)
+
+
+def test_encode_decode_round_trip_ties_and_accumulation():
+    rng = np.random.default_rng(24)
+    M, Ds = 2, 3
+    cw = rng.normal(size=(M, 256, Ds)).astype(np.float32)
+    cw[0, 200] = cw[0, 7]                                   # a duplicated codeword: the lower index wins
+    codes = rng.integers(0, 256, size=(500, M), dtype=np.uint8)
+    codes[:5, 0] = 200
+    rec = oracle.decode_f32(cw, codes)
+    np.testing.assert_array_equal(rec.reshape(500, M, Ds)[:, 1], cw[1][codes[:, 1]])      # decode = fetch codewords
+    np.testing.assert_array_equal(rec.astype(np.float64), oracle.decode(cw, codes))
+    back, d2 = oracle.encode(rec, cw, want_dist=True)
+    expect = codes.copy()
+    expect[expect[:, 0] == 200, 0] = 7
+    np.testing.assert_array_equal(back, expect)             # a codeword encodes to itself, at distance exactly 0
+    assert (d2 == 0).all()
+    # the accumulation is one fused multiply-add per dimension in ascending order: vectors for which fused and
+    # unfused accumulation, or ascending and descending order, give different bits (found by search, checked
+    # against exact rational arithmetic rounded once per operation)
+    c1 = np.zeros((1, 256, 3), np.float32)
+    c1[0, 1:] = 1e6
+    seen_unfused = seen_order = 0
+    for trial in range(200):
+        x = rng.normal(size=(1, 3)).astype(np.float32)
+        _, got = oracle.encode(x, c1, want_dist=True)
+
+        def chain(order, fused):
+            acc = Fraction(0)
+            for d in order:
+                t = _round_f32(Fraction(float(x[0, d])) - Fraction(float(c1[0, 0, d])))
+                sq = Fraction(float(t)) ** 2
+                acc = Fraction(float(_round_f32(sq + acc))) if fused else \
+                    Fraction(float(_round_f32(Fraction(float(_round_f32(sq))) + acc)))
+            return np.float32(float(acc))
+
+        assert got[0, 0] == chain((0, 1, 2), True)
+        seen_unfused += got[0, 0] != chain((0, 1, 2), False)
+        seen_order += got[0, 0] != chain((2, 1, 0), True)
+    assert seen_unfused > 10 and seen_order > 10
