@@ -31,6 +31,43 @@ LDS_PEAK_GBS = 256 * 2.4e9 * 256 / 1e9          # 157286 GB/s: 256 CUs x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 
 
+FP32_VALU_PEAK_TFLOPS = 157.3                    # published fp32 vector peak (fused multiply-adds, packed)
+
+
+def encoder_bench(args, w, pq, torch, dev) -> int:
+    """PQ encoding of min(N, 2^20) random vectors of the configuration's dimensionality; HIP events on the
+    stream the kernel runs on."""
+    import workloads as W
+
+    n = min(w.N, 1 << 20)
+    Ds = w.D // w.M
+    cw = torch.from_numpy(W.codewords(w)).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    vectors = torch.randn((n, w.D), generator=gen, device=dev, dtype=torch.float32)
+    codes = torch.empty((n, w.M), dtype=torch.uint8, device=dev)
+    for _ in range(max(args.warmup, 1)):
+        pq.encode(vectors, cw, codes=codes)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    steps = max(1, min(args.steps, 20))
+    e0.record()
+    for _ in range(steps):
+        pq.encode(vectors, cw, codes=codes)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    flops = 3.0 * n * w.D * 256                    # one subtraction and one fused multiply-add per (vector, codeword, dim)
+    tflops = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "PQ encoding (Sec. 2.2), vectors/s", "value": n / (ms * 1e-3), "unit": "vectors/s", "n_gpus": 1,
+        "steps": steps, "ms_per_step": ms, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"encoder, config {args.config} shape: {n} vectors, D={w.D}, M={w.M}, Ds={Ds}, L=256"},
+        "roofline": {"bound": "alu", "kernel": "encode_kernel", "achieved": tflops, "peak": FP32_VALU_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tflops / FP32_VALU_PEAK_TFLOPS, "traffic": None},
+        "hbm_gbs": n * w.D * 4 / (ms * 1e-3) / 1e9}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +75,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload configuration (1-5); 2 is the benchmark's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--encoder", action="store_true",
+                    help="time the PQ encoder (Sec. 2.2), the preprocessing step in front of the clustering, on "
+                         "random vectors of the configuration's shape instead of the iteration; prints its own line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 1 GiB (5 times): the known-size kernel against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -67,6 +107,8 @@ def main() -> int:
         return 0
     w = W.CONFIGS[args.config]
     N, M, K = w.N, w.M, w.K
+    if args.encoder:
+        return encoder_bench(args, w, pq, torch, dev)
 
     cw = W.codewords(w)
     tables = pq.build_tables(torch.from_numpy(cw).to(dev))

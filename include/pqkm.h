@@ -73,6 +73,24 @@ pqkm_status pqkm_build_tables(const float *codewords, int32_t M, int32_t Ds, flo
                               void *stream);
 
 /*
+ * Product-quantisation encoding (Sec. 2.2): every one of the M subvectors (Ds consecutive
+ * components) of a vector is replaced by the index of its closest codeword,
+ *   codes[n][m] = argmin_l  sum_{d} (vectors[n][m*Ds + d] - codewords[m][l][d])^2,
+ * lowest l on ties.  The sum is accumulated in fp32 over ascending d with one fp32 subtraction
+ * and one fused multiply-add per component, which makes the result unique.
+ *   vectors    [N][M*Ds] fp32, in       codewords [M][256][Ds] fp32, in
+ *   codes      [N][M] u8, out
+ * This is the preprocessing step in front of the clustering; N = 0 is legal.
+ *
+ * pqkm_decode is the reconstruction of Sec. 2.2: vectors[n][m*Ds + d] = codewords[m][codes[n][m]][d].
+ *   codes      [N][M] u8, in            vectors   [N][M*Ds] fp32, out
+ */
+pqkm_status pqkm_encode(const float *vectors, int64_t N, int32_t M, int32_t Ds, const float *codewords,
+                        uint8_t *codes, void *stream);
+pqkm_status pqkm_decode(const uint8_t *codes, int64_t N, int32_t M, int32_t Ds, const float *codewords,
+                        float *vectors, void *stream);
+
+/*
  * Assignment step (Eq. 5 with the squared symmetric distance of Eq. 3):
  *   assign[n] = argmin_k  sum_{m} tables[m][codes[n][m]][centers[k][m]]
  * lowest k on ties.

@@ -39,10 +39,12 @@ def load():
         lib.pqkm_fit_until_workspace_bytes.restype = sz
         lib.pqkm_fit_until_workspace_bytes.argtypes = [i64, i32, i32]
         lib.pqkm_fit_until.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.pqkm_encode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        lib.pqkm_decode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
-                  "pqkm_profile_read"):
+                  "pqkm_profile_read", "pqkm_encode", "pqkm_decode"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -102,6 +104,36 @@ def build_tables(codewords, tables=None):
     _need(tables, torch.float32, (M, L, L), "tables")
     _check(load().pqkm_build_tables(_ptr(codewords), M, Ds, _ptr(tables), _stream()), "pqkm_build_tables")
     return tables
+
+
+def encode(vectors, codewords, codes=None):
+    """vectors [N][M*Ds] f32, codewords [M][256][Ds] f32 -> codes [N][M] u8 (Sec. 2.2)."""
+    import torch
+
+    M, l, Ds = codewords.shape
+    N = vectors.shape[0]
+    _need(codewords, torch.float32, (M, L, Ds), "codewords")
+    _need(vectors, torch.float32, (N, M * Ds), "vectors")
+    if codes is None:
+        codes = torch.empty((N, M), dtype=torch.uint8, device=vectors.device)
+    _need(codes, torch.uint8, (N, M), "codes")
+    _check(load().pqkm_encode(_ptr(vectors), N, M, Ds, _ptr(codewords), _ptr(codes), _stream()), "pqkm_encode")
+    return codes
+
+
+def decode(codes, codewords, vectors=None):
+    """codes [N][M] u8 -> reconstructed vectors [N][M*Ds] f32 (Sec. 2.2)."""
+    import torch
+
+    M, l, Ds = codewords.shape
+    N = codes.shape[0]
+    _need(codewords, torch.float32, (M, L, Ds), "codewords")
+    _need(codes, torch.uint8, (N, M), "codes")
+    if vectors is None:
+        vectors = torch.empty((N, M * Ds), dtype=torch.float32, device=codes.device)
+    _need(vectors, torch.float32, (N, M * Ds), "vectors")
+    _check(load().pqkm_decode(_ptr(codes), N, M, Ds, _ptr(codewords), _ptr(vectors), _stream()), "pqkm_decode")
+    return vectors
 
 
 def assign(codes, centers, tables, assign=None, dist=None, want_dist=True, workspace=None):

@@ -512,6 +512,14 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     return launched();
 }
 
+template <int DS>
+void launch_encode(const float* vectors, int64_t N, int M, const float* codewords, uint8_t* codes, hipStream_t st)
+{
+    constexpr int TH = DS >= 64 ? 512 : 256;
+    hipLaunchKernelGGL((encode_kernel<DS, TH>), dim3((unsigned)((N + TH - 1) / TH), (unsigned)M), dim3(TH),
+                       (size_t)L * DS * sizeof(float), st, vectors, N, M, codewords, codes);
+}
+
 }  // namespace
 
 extern "C" {
@@ -542,6 +550,44 @@ pqkm_status pqkm_build_tables(const float* codewords, int32_t M, int32_t Ds, flo
     if (s != PQKM_OK) return s;
     hipLaunchKernelGGL(build_tables_kernel, dim3(L, M), dim3(256), (size_t)Ds * sizeof(float), (hipStream_t)stream,
                        codewords, Ds, tables);
+    return launched();
+}
+
+pqkm_status pqkm_encode(const float* vectors, int64_t N, int32_t M, int32_t Ds, const float* codewords,
+                        uint8_t* codes, void* stream)
+{
+    if (N < 0 || M < 1 || M > 64 || Ds < 1 || Ds > 12288 || N > (int64_t)0x7fffffff * 256) return PQKM_ERR_SHAPE;
+    if (!codewords || (N > 0 && (!vectors || !codes))) return PQKM_ERR_NULL;
+    pqkm_status s = check_device();
+    if (s != PQKM_OK) return s;
+    if (N == 0) return PQKM_OK;
+    hipStream_t st = (hipStream_t)stream;
+    switch (Ds) {
+        case 4: launch_encode<4>(vectors, N, M, codewords, codes, st); break;
+        case 8: launch_encode<8>(vectors, N, M, codewords, codes, st); break;
+        case 16: launch_encode<16>(vectors, N, M, codewords, codes, st); break;
+        case 32: launch_encode<32>(vectors, N, M, codewords, codes, st); break;
+        case 64: launch_encode<64>(vectors, N, M, codewords, codes, st); break;
+        case 128: launch_encode<128>(vectors, N, M, codewords, codes, st); break;
+        default:
+            hipLaunchKernelGGL(encode_generic_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, st,
+                               vectors, N, M, Ds, codewords, codes);
+    }
+    return launched();
+}
+
+pqkm_status pqkm_decode(const uint8_t* codes, int64_t N, int32_t M, int32_t Ds, const float* codewords,
+                        float* vectors, void* stream)
+{
+    if (N < 0 || M < 1 || M > 64 || Ds < 1 || Ds > 12288) return PQKM_ERR_SHAPE;
+    if (!codewords || (N > 0 && (!vectors || !codes))) return PQKM_ERR_NULL;
+    pqkm_status s = check_device();
+    if (s != PQKM_OK) return s;
+    if (N == 0) return PQKM_OK;
+    const int64_t total = N * M * Ds;
+    if ((total + 255) / 256 > (int64_t)0x7fffffff) return PQKM_ERR_SHAPE;
+    hipLaunchKernelGGL(decode_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, codes,
+                       total, M, Ds, codewords, vectors);
     return launched();
 }
 

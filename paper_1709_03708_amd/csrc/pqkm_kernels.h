@@ -41,6 +41,93 @@ __global__ __launch_bounds__(256) void build_tables_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// Sec. 2.2, encoding: every subvector is replaced by the index of its closest codeword.  Distance:
+// fp32, ascending dimension, one subtraction and one fused multiply-add per dimension (explicit
+// fmaf; the file is compiled without contraction); ties go to the lowest index (strict "<" over
+// ascending l).  Grid (blocks of THREADS vectors, M), one thread per vector: the subvector sits in
+// registers, the 256 codewords of the subspace in LDS (read as wave-uniform broadcasts, four
+// codewords in flight for instruction-level parallelism; long subvectors use 512 threads so that
+// every SIMD has two waves to alternate between).  Plain VALU work, 3 flops per
+// (vector, codeword, dimension); an MFMA formulation through ||x||^2 - 2 x.c + ||c||^2 would round
+// differently and could not be compared bit for bit.
+// ---------------------------------------------------------------------------------------------
+template <int DS, int THREADS>
+__global__ __launch_bounds__(THREADS) void encode_kernel(const float* __restrict__ vectors, int64_t N, int M,
+                                                     const float* __restrict__ codewords,
+                                                     uint8_t* __restrict__ codes)
+{
+    extern __shared__ float cw[];                          // [256][DS]
+    const int m = blockIdx.y;
+    const float* src = codewords + (size_t)m * L * DS;
+    for (int i = threadIdx.x; i < L * DS; i += THREADS) cw[i] = src[i];
+    __syncthreads();
+    const int64_t n = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+    if (n >= N) return;
+    float x[DS];
+    const float* xv = vectors + ((size_t)n * M + m) * DS;
+#pragma unroll
+    for (int d = 0; d < DS; ++d) x[d] = xv[d];
+    float best = INFINITY;
+    int bl = 0;
+    for (int l0 = 0; l0 < L; l0 += 4) {
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int d = 0; d < DS; ++d) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float t = x[d] - cw[(l0 + u) * DS + d];
+                acc[u] = __builtin_fmaf(t, t, acc[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (acc[u] < best) {
+                best = acc[u];
+                bl = l0 + u;
+            }
+    }
+    codes[n * M + m] = (uint8_t)bl;
+}
+
+// any subvector length: same arithmetic, operands read through the caches
+__global__ __launch_bounds__(256) void encode_generic_kernel(const float* __restrict__ vectors, int64_t N, int M,
+                                                             int Ds, const float* __restrict__ codewords,
+                                                             uint8_t* __restrict__ codes)
+{
+    const int m = blockIdx.y;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const float* xv = vectors + ((size_t)n * M + m) * Ds;
+    float best = INFINITY;
+    int bl = 0;
+    for (int l = 0; l < L; ++l) {
+        const float* c = codewords + ((size_t)m * L + l) * Ds;
+        float acc = 0.0f;
+        for (int d = 0; d < Ds; ++d) {
+            const float t = xv[d] - c[d];
+            acc = __builtin_fmaf(t, t, acc);
+        }
+        if (acc < best) {
+            best = acc;
+            bl = l;
+        }
+    }
+    codes[n * M + m] = (uint8_t)bl;
+}
+
+// Sec. 2.2, reconstruction: a code decodes to the concatenation of its codewords.  One thread per output element.
+__global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ codes, int64_t total, int M, int Ds,
+                                                     const float* __restrict__ codewords, float* __restrict__ out)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int d = (int)(e % Ds);
+    const int64_t nm = e / Ds;
+    const int m = (int)(nm % M);
+    out[e] = codewords[((size_t)m * L + codes[nm]) * Ds + d];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Generic assignment (any M): one lane per code, centers read wave-uniformly, table entries
 // gathered through the cache hierarchy.  Eq. 5 exactly as written: ascending k, strict <.
 // ---------------------------------------------------------------------------------------------

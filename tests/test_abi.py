@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared()
     assert {"pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_workspace_bytes",
             "pqkm_status_string", "pqkm_set_option", "pqkm_profile_read", "pqkm_fit_until",
-            "pqkm_fit_until_workspace_bytes"} <= set(names)
+            "pqkm_fit_until_workspace_bytes", "pqkm_encode", "pqkm_decode"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -50,7 +50,8 @@ def test_workspace_bytes_is_host_arithmetic(lib):
     b = pq.workspace_bytes(10**6, 4, 1000)
     assert b >= 32 * 131072 + 1000 * 4 * 256 * 4 + 1000 * 4
     assert b % 256 == 0
-    assert pq.workspace_bytes(10**9, 4, 10**5) < 2**31     # well under a GiB
+    # config 5: 4 bytes per code of sorted indices, two copies of the tile images, one launch of regrouped codes
+    assert 4 * 10**9 <= pq.workspace_bytes(10**9, 4, 10**5) < 6 * 2**30
     assert pq.fit_until_workspace_bytes(10**6, 4, 1000) >= b + 8 * 10**6
     # a generic M needs no tile images
     assert pq.workspace_bytes(100, 5, 10) < 131072
@@ -81,6 +82,14 @@ def test_bad_arguments_are_rejected_before_any_gpu_work(lib):
     assert lib.pqkm_fit_until(one, 10, 4, one, 5, one, -1, one, null, null, null, null, one, 1 << 30, null) == SHAPE
     assert lib.pqkm_fit_until(one, 10, 4, null, 5, one, 3, one, null, null, null, null, one, 1 << 30, null) == NULL
     assert lib.pqkm_fit_until(one, 10, 4, one, 5, one, 3, one, null, null, null, null, one, 64, null) == WS
+    for f in (lib.pqkm_encode, lib.pqkm_decode):
+        f.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
+        f.restype = ctypes.c_int
+        assert f(one, 10, 0, 32, one, one, null) == SHAPE
+        assert f(one, 10, 4, 0, one, one, null) == SHAPE
+        assert f(one, -1, 4, 32, one, one, null) == SHAPE
+        assert f(one, 10, 4, 32, null, one, null) == NULL
+        assert f(null, 10, 4, 32, one, one, null) == NULL
     assert lib.pqkm_build_tables(null, 4, 32, one, null) == NULL
     assert lib.pqkm_build_tables(one, 4, 0, one, null) == SHAPE
     assert lib.pqkm_build_tables(one, 0, 32, one, null) == SHAPE

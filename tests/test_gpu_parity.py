@@ -446,3 +446,32 @@ def test_config4_cnn_sampled(env):
 
 def test_config5_billion_sampled(env):
     _run_config_sampled(env, 5, 100_000, iters=1)
+
+
+# ------------------------------------------------------------------------------------ encode / decode (Sec. 2.2)
+@pytest.mark.parametrize("M,Ds,N", [(4, 32, 5003), (8, 16, 3000), (32, 128, 700), (2, 64, 1025), (3, 5, 2001), (1, 1, 300),
+                                    (4, 8, 1), (2, 4, 257), (1, 200, 300)])
+def test_encode_decode_match_oracle(env, M, Ds, N):
+    """Bit-exact codes (every compiled subvector length and the generic kernel), including vectors that are
+    codewords (distance 0, duplicated codeword -> lowest index) and integer data with many exact ties."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(M * 1000 + Ds)
+    cw = rng.normal(size=(M, 256, Ds)).astype(np.float32)
+    cw[0, 255] = cw[0, 3]
+    v = rng.normal(size=(N, M * Ds)).astype(np.float32)
+    v[: min(N, 40)] = oracle.decode_f32(cw, rng.integers(0, 256, size=(min(N, 40), M), dtype=np.uint8))
+    for vectors, codewords in ((v, cw), (np.rint(v * 2).astype(np.float32), np.rint(cw * 2).astype(np.float32))):
+        codes = pq.encode(_dev(env, vectors), _dev(env, codewords))
+        _sync(env)
+        ref = oracle.encode(vectors, codewords)
+        np.testing.assert_array_equal(codes.cpu().numpy(), ref)
+        rec = pq.decode(codes, _dev(env, codewords))
+        _sync(env)
+        np.testing.assert_array_equal(rec.cpu().numpy().view(np.uint32), oracle.decode_f32(codewords, ref).view(np.uint32))
+
+
+def test_encode_empty_input(env):
+    pq, torch, dev = env["pq"], env["torch"], env["dev"]
+    cw = torch.zeros((4, 256, 32), dtype=torch.float32, device=dev)
+    assert pq.encode(torch.empty((0, 128), dtype=torch.float32, device=dev), cw).shape == (0, 4)
+    assert pq.decode(torch.empty((0, 4), dtype=torch.uint8, device=dev), cw).shape == (0, 128)
