@@ -68,6 +68,46 @@ def encoder_bench(args, w, pq, torch, dev) -> int:
     return 0
 
 
+def naive_update_bench(args, w, pq, torch, dev) -> int:
+    """Update step alone, sparse voting against the naive method, on the assignment of the first iteration."""
+    import workloads as W
+
+    n = min(w.N, 1 << 24)
+    wl = w if n == w.N else __import__("dataclasses").replace(w, N=n)
+    tables = pq.build_tables(torch.from_numpy(W.codewords(wl)).to(dev))
+    codes = W.codes_torch(wl, dev)
+    centers0 = torch.from_numpy(W.codes_at(wl, W.init_center_indices(wl))).to(dev)
+    ws = torch.empty(pq.workspace_bytes(n, wl.M, wl.K), dtype=torch.uint8, device=dev)
+    assign, _ = pq.assign(codes, centers0, tables, want_dist=False, workspace=ws)
+    hist = torch.empty((wl.K, wl.M, 256), dtype=torch.int32, device=dev)
+    steps = max(1, min(args.steps, 20))
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    c1, c2 = centers0.clone(), centers0.clone()
+    ms_sparse = timed(lambda: (c1.copy_(centers0), pq.update(codes, assign, tables, c1, hist=hist, workspace=ws)))
+    ms_naive = timed(lambda: (c2.copy_(centers0), pq.update_naive(codes, assign, tables, c2, workspace=ws)))
+    torch.cuda.synchronize()
+    nz = float((hist != 0).sum()) / (wl.K * wl.M)
+    print(json.dumps({
+        "metric": "update step: sparse voting (Eq. 7-8) vs naive (Eq. 6)", "value": ms_naive / ms_sparse,
+        "unit": "x (naive time / sparse-voting time)", "n_gpus": 1, "steps": steps, "dtype": "f32 vote, f64 naive sums",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: N={n}, M={wl.M}, K={wl.K}; assignment of the first iteration"},
+        "ms_sparse_voting": ms_sparse, "ms_naive": ms_naive, "mean_nonzero_bins": nz,
+        "same_centers": bool((c1 == c2).all())}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +118,9 @@ def main() -> int:
     ap.add_argument("--encoder", action="store_true",
                     help="time the PQ encoder (Sec. 2.2), the preprocessing step in front of the clustering, on "
                          "random vectors of the configuration's shape instead of the iteration; prints its own line")
+    ap.add_argument("--naive-update", action="store_true",
+                    help="time the sparse-voting update (Eq. 7-8) against the naive update (Eq. 6) on the "
+                         "configuration's first assignment, as in the paper's per-step runtime table; prints its own line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 1 GiB (5 times): the known-size kernel against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -109,6 +152,8 @@ def main() -> int:
     N, M, K = w.N, w.M, w.K
     if args.encoder:
         return encoder_bench(args, w, pq, torch, dev)
+    if args.naive_update:
+        return naive_update_bench(args, w, pq, torch, dev)
 
     cw = W.codewords(w)
     tables = pq.build_tables(torch.from_numpy(cw).to(dev))

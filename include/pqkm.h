@@ -119,6 +119,21 @@ pqkm_status pqkm_update(const uint8_t *codes, int64_t N, int32_t M, const int32_
                         uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The naive update (Eq. 6), the method sparse voting is measured against (Sec. 3.2, Tab. 3):
+ *   cost[k][m][l] = sum over the members n of cluster k of tables[m][codes[n][m]][l]
+ *   centers[k][m] <- argmin_l cost[k][m][l], lowest l on ties; empty clusters keep their code.
+ * O(256 M N) table entries instead of the vote's O(M (N + K 256 ||h||_0)).  The sums are fp64, taken in
+ * the order a counting sort leaves the members in, which is not fixed: they are reproducible up to
+ * fp64 rounding, and exactly when the table entries are integers.  With exact sums the result is
+ * that of pqkm_update.
+ *   cost   [K][M][256] fp64, out, may be NULL
+ * N must be below 2^32.  Arguments otherwise as for pqkm_update.
+ */
+pqkm_status pqkm_update_naive(const uint8_t *codes, int64_t N, int32_t M, const int32_t *assign,
+                              int32_t K, const float *tables, uint8_t *centers, double *cost,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Alg. 1 with the linear scan and a fixed iteration count:
  *   repeat iters times { pqkm_assign ; pqkm_update }.
  * Init() is the caller's: `centers` holds the initial centers on entry and the

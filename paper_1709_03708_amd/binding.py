@@ -39,12 +39,13 @@ def load():
         lib.pqkm_fit_until_workspace_bytes.restype = sz
         lib.pqkm_fit_until_workspace_bytes.argtypes = [i64, i32, i32]
         lib.pqkm_fit_until.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.pqkm_update_naive.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.pqkm_encode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.pqkm_decode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
-                  "pqkm_profile_read", "pqkm_encode", "pqkm_decode"):
+                  "pqkm_profile_read", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -177,6 +178,23 @@ def update(codes, assign, tables, centers, hist=None, counts=None, want_hist=Tru
     _check(load().pqkm_update(_ptr(codes), N, M, _ptr(assign), K, _ptr(tables), _ptr(centers), _ptr(hist),
                               _ptr(counts), _ptr(workspace), wb, _stream()), "pqkm_update")
     return centers, hist, counts
+
+
+def update_naive(codes, assign, tables, centers, want_cost=False, workspace=None):
+    """Eq. 6 by brute force, in place on ``centers``; -> (centers, cost [K][M][256] f64 or None)."""
+    import torch
+
+    N, M = codes.shape
+    K = centers.shape[0]
+    _need(codes, torch.uint8, (N, M), "codes")
+    _need(assign, torch.int32, (N,), "assign")
+    _need(centers, torch.uint8, (K, M), "centers")
+    _need(tables, torch.float32, (M, L, L), "tables")
+    cost = torch.empty((K, M, L), dtype=torch.float64, device=codes.device) if want_cost else None
+    workspace, wb = _ws(workspace, N, M, K, codes.device)
+    _check(load().pqkm_update_naive(_ptr(codes), N, M, _ptr(assign), K, _ptr(tables), _ptr(centers), _ptr(cost),
+                                    _ptr(workspace), wb, _stream()), "pqkm_update_naive")
+    return centers, cost
 
 
 def fit(codes, tables, centers, iters, assign=None, hist=None, counts=None, workspace=None):

@@ -436,6 +436,28 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
     }
 }
 
+// counting sort of the code indices by cluster into the workspace: start[0..K] and sidx[0..#valid)
+void sort_by_cluster(const int32_t* assign, int64_t N, int K, const Carve& c, char* ws, uint32_t** start_out,
+                     uint32_t** sidx_out, hipStream_t st)
+{
+    const size_t seg_stride = align256(((size_t)K + 1) * sizeof(uint32_t));
+    uint32_t* sidx = reinterpret_cast<uint32_t*>(ws + c.sidx_off);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + c.seg_off);
+    uint32_t* start = reinterpret_cast<uint32_t*>(ws + c.seg_off + seg_stride);
+    uint32_t* cursor = reinterpret_cast<uint32_t*>(ws + c.seg_off + 2 * seg_stride);
+    unsigned zb = (unsigned)((K + 255) / 256 < 1024 ? (K + 255) / 256 : 1024);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, cnt, (int64_t)K);
+    unsigned cb = (unsigned)((N + 4095) / 4096 < 1024 ? (N + 4095) / 4096 : 1024);
+    if (cb < 1) cb = 1;
+    hipLaunchKernelGGL(seg_count_kernel, dim3(cb), dim3(1024), 0, st, assign, N, K, cnt);
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, K, start, cursor);
+    unsigned sb = (unsigned)((N + 1023) / 1024 < 8192 ? (N + 1023) / 1024 : 8192);
+    if (sb < 1) sb = 1;
+    hipLaunchKernelGGL(seg_scatter_kernel, dim3(sb), dim3(256), 0, st, assign, N, K, start, cursor, sidx);
+    *start_out = start;
+    *sidx_out = sidx;
+}
+
 pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* assign, int K, const float* tables,
                         uint8_t* centers, uint32_t* hist, uint32_t* counts, void* ws, hipStream_t st)
 {
@@ -477,18 +499,8 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
                                0, st, codes, N, M, assign, gid, K, hp.KT, S, parts, part_stride);
     } else if (force != 1 && N <= (int64_t)0xffffffff && N > 0 && M <= 128) {
         // sorted path: counting sort of the code indices by cluster, then LDS histograms per stretch of clusters
-        const size_t seg_stride = align256(((size_t)K + 1) * sizeof(uint32_t));
-        uint32_t* sidx = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.sidx_off);
-        uint32_t* cnt = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off);
-        uint32_t* start = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off + seg_stride);
-        uint32_t* cursor = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.seg_off + 2 * seg_stride);
-        unsigned zb = (unsigned)((K + 255) / 256 < 1024 ? (K + 255) / 256 : 1024);
-        hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, cnt, (int64_t)K);
-        unsigned cb = (unsigned)((N + 4095) / 4096 < 1024 ? (N + 4095) / 4096 : 1024);
-        hipLaunchKernelGGL(seg_count_kernel, dim3(cb), dim3(1024), 0, st, assign, N, K, cnt);
-        hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, K, start, cursor);
-        unsigned sb = (unsigned)((N + 1023) / 1024 < 8192 ? (N + 1023) / 1024 : 8192);
-        hipLaunchKernelGGL(seg_scatter_kernel, dim3(sb), dim3(256), 0, st, assign, N, K, start, cursor, sidx);
+        uint32_t *start, *sidx;
+        sort_by_cluster(assign, N, K, c, static_cast<char*>(ws), &start, &sidx, st);
         int KT = (HIST_LDS_WORDS / L) / M;
         if (KT > 128) KT = 128;
         hipLaunchKernelGGL(seg_hist_kernel, dim3((unsigned)((K + KT - 1) / KT)), dim3(1024), 0, st, codes, M, start, sidx,
@@ -613,6 +625,25 @@ pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_
     if (s != PQKM_OK) return s;
     if ((s = check_device()) != PQKM_OK) return s;
     return update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
+}
+
+pqkm_status pqkm_update_naive(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,
+                              const float* tables, uint8_t* centers, double* cost, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    if (!shape_ok(N, M, K) || N > (int64_t)0xffffffff) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    const Carve c = carve(N, M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, c.total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t *start, *sidx;
+    sort_by_cluster(assign, N, K, c, static_cast<char*>(workspace), &start, &sidx, st);
+    // grid (K, M): K up to 2^31 - 1 fits the x dimension
+    hipLaunchKernelGGL(naive_update_kernel, dim3((unsigned)K, (unsigned)M), dim3(256), 0, st, codes, M, start, sidx,
+                       tables, centers, cost);
+    return launched();
 }
 
 pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* tables, int32_t K, uint8_t* centers,

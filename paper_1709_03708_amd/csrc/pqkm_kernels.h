@@ -1814,6 +1814,51 @@ __global__ __launch_bounds__(1024) void seg_hist_kernel(const uint8_t* __restric
 }
 
 // ---------------------------------------------------------------------------------------------
+// Eq. 6, the naive update (kept as the comparison the paper measures sparse voting against): for
+// every cluster and subspace all 256 candidates are tested against all members,
+//   cost[k][m][l] = sum over members n of A^m[x_n^m][l],   centers[k][m] = argmin_l cost (lowest l),
+// O(L M N) table entries.  Workgroup (k, m), thread = candidate l: the members' indices come from
+// the same counting sort as the sorted-path histogram, each member contributes one 1 KB table
+// row (a coalesced read), sums are fp64.  The order of the members inside a cluster is whatever
+// the sort's atomics left, so the sums are reproducible only up to fp64 rounding (exactly, when
+// the table entries are integers).  Empty clusters keep their code.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void naive_update_kernel(const uint8_t* __restrict__ codes, int M,
+                                                           const uint32_t* __restrict__ start,
+                                                           const uint32_t* __restrict__ sidx,
+                                                           const float* __restrict__ tables,
+                                                           uint8_t* __restrict__ centers, double* __restrict__ cost_out)
+{
+    __shared__ double sv[256];
+    __shared__ int si[256];
+    const int k = blockIdx.x, m = blockIdx.y, l = threadIdx.x;
+    const uint32_t p0 = start[k], p1 = start[k + 1];
+    const float* A = tables + (size_t)m * L * L;
+    double acc = 0.0;
+    for (uint32_t p = p0; p < p1; ++p) {
+        const uint32_t x = codes[(size_t)sidx[p] * M + m];
+        acc = acc + (double)A[x * L + l];
+    }
+    if (cost_out) cost_out[((size_t)k * M + m) * L + l] = acc;
+    if (p0 == p1) return;                            // wave-uniform: the whole workgroup leaves
+    sv[l] = acc;
+    si[l] = l;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+        if (l < off) {
+            const double ov = sv[l + off];
+            const int oi = si[l + off];
+            if (ov < sv[l] || (ov == sv[l] && oi < si[l])) {
+                sv[l] = ov;
+                si[l] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (l == 0) centers[(size_t)k * M + m] = (uint8_t)si[0];
+}
+
+// ---------------------------------------------------------------------------------------------
 // Eq. 7, owner path: LDS-privatised histograms, no global atomics.
 //
 // Clusters are grouped KT at a time, KT chosen so that there are up to 255 groups (about one

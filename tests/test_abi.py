@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared()
     assert {"pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_workspace_bytes",
             "pqkm_status_string", "pqkm_set_option", "pqkm_profile_read", "pqkm_fit_until",
-            "pqkm_fit_until_workspace_bytes", "pqkm_encode", "pqkm_decode"} <= set(names)
+            "pqkm_fit_until_workspace_bytes", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

@@ -475,3 +475,43 @@ def test_encode_empty_input(env):
     cw = torch.zeros((4, 256, 32), dtype=torch.float32, device=dev)
     assert pq.encode(torch.empty((0, 128), dtype=torch.float32, device=dev), cw).shape == (0, 4)
     assert pq.decode(torch.empty((0, 4), dtype=torch.uint8, device=dev), cw).shape == (0, 128)
+
+
+# ------------------------------------------------------------------------------------ naive update (Eq. 6)
+@pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 20_000), (3, 11, 700), (4, 1000, 100_000)])
+def test_update_naive_matches_oracle(env, M, K, N):
+    """Integer tables: every sum is exact, so centers and cost sums equal the oracle's bit for bit whatever the
+    order of the members.  Real tables: the sums agree to fp64 rounding (the member order is not fixed) and the
+    centers are the oracle's except where two candidates tie to within that rounding; both equal the sparse vote's
+    centers under the same rule (the paper's exactness claim, Sec. 3.2)."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(M * K + 1)
+    codes = rng.integers(0, 40, size=(N, M), dtype=np.uint8)
+    a = rng.integers(0, K - 1, size=N).astype(np.int32)               # last cluster stays empty
+    centers = rng.integers(0, 256, size=(K, M), dtype=np.uint8)
+    for integer in (True, False):
+        tables = rand_tables(rng, M, integer=integer)
+        d_cent = _dev(env, centers)
+        _, cost = pq.update_naive(_dev(env, codes), _dev(env, a), _dev(env, tables), d_cent, want_cost=True)
+        _sync(env)
+        got, cost = d_cent.cpu().numpy(), cost.cpu().numpy()
+        rc, rcost = oracle.update_naive(codes, a, tables, centers, want_cost=True)
+        assert (got[K - 1] == centers[K - 1]).all()
+        if integer:
+            np.testing.assert_array_equal(cost, rcost)
+            np.testing.assert_array_equal(got, rc)
+        else:
+            np.testing.assert_allclose(cost, rcost, rtol=1e-12, atol=0)
+            diff = np.argwhere(got != rc)
+            for k, m in diff:                                         # only exact-tie-level differences are allowed
+                assert abs(rcost[k, m, got[k, m]] - rcost[k, m, rc[k, m]]) <= 1e-12 * rcost[k, m, rc[k, m]]
+            assert len(diff) <= 2
+        d2 = _dev(env, centers)
+        pq.update(_dev(env, codes), _dev(env, a), _dev(env, tables), d2)
+        _sync(env)
+        sparse = d2.cpu().numpy()
+        if integer:
+            np.testing.assert_array_equal(sparse, got)
+        else:
+            for k, m in np.argwhere(sparse != got):                    # fp32 vote vs fp64 sums: near-ties only
+                assert abs(rcost[k, m, sparse[k, m]] - rcost[k, m, got[k, m]]) <= 1e-5 * rcost[k, m, got[k, m]]
