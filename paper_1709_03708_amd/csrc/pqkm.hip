@@ -517,9 +517,11 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     // vote: one workgroup per (subspace, CW clusters); about a thousand workgroups, at least one cluster per wave
     int64_t cw = ((int64_t)K * M + 1023) / 1024;
     cw = ((cw + 15) / 16) * 16;
+    constexpr int vote_pass = VOTE_WAVES * VOTE_CPW;
+    if (cw > 16) cw = ((cw + vote_pass - 1) / vote_pass) * vote_pass;   // whole passes of the waves
     if (cw > VOTE_MAX_CW) cw = VOTE_MAX_CW;
     const int64_t blocks_per_m = ((int64_t)K + cw - 1) / cw;
-    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)(blocks_per_m * M)), dim3(1024), 0, st, hist, parts, S, part_stride,
+    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)(blocks_per_m * M)), dim3(VOTE_THREADS), 0, st, hist, parts, S, part_stride,
                        counts, K, M, (int)cw, tables, centers);
     return launched();
 }

@@ -2014,128 +2014,175 @@ __global__ __launch_bounds__(1024) void histogram_owner_kernel(const uint8_t* __
 // Eq. 8: sparse vote with the table in LDS.
 //
 // A workgroup (1024 threads = 16 waves) serves one subspace m and CW consecutive clusters.  It
-// holds half of A^m in LDS -- A^m[j][l] for all 256 member bins j and 128 of the 256 candidates
-// l (128 KB) -- and runs twice, once per candidate half.  A wave takes one cluster at a time:
-// it first compacts the non-zero bins of the cluster's histogram, in ascending j, into a small
-// per-wave list in LDS (bin index and count as fp32; ballot + prefix popcount), then walks the
-// list: lane i owns candidates 2i, 2i+1 of the half, and every list entry costs two broadcast
-// LDS reads, one conflict-free 512-byte row read and one fmaf per candidate (v accumulates in
-// fp32 from 0, in ascending j, exactly as Eq. 8 is read here).  The 128-way argmin is a per-lane
-// ascending strict "<" and a (value, index) xor-shuffle merge; the first half's winner is parked
-// in LDS and the second half replaces it only if strictly smaller, so the lowest index wins
-// ties.  The cluster size is the sum of the bins (the same for every subspace): an empty cluster
-// keeps its code, and subspace 0 stores the size to counts[k].  If the histogram arrives as
-// S > 1 partial arrays they are added while loading (integer, exact) and the total is stored to
-// hist during the first half.
+// holds half of A^m in LDS -- the rows A^m[j][.] of 128 member bins j, all 256 candidates l each
+// (128 KB) -- and runs twice, once per half of the bins; the rows of the second half travel to
+// registers while the first is in use.  A wave takes VOTE_CPW clusters per pass and keeps their
+// 256 running sums in registers across the two halves: lane i owns the candidates 4i .. 4i+3,
+// v accumulates in fp32 from 0 in ascending j with one fmaf per non-zero bin, exactly as Eq. 8 is
+// read here, and every bin is visited once.  The non-zero bins are not compacted to a list: the
+// wave walks the set bits of the ballot (h_j != 0) in ascending order, takes the count of bin j
+// from its lane (a scalar), reads row j (one conflict-free 16-byte read per lane) and issues
+// four fmaf.  The 256-way argmin is a per-lane ascending strict "<" and a (value, index)
+// xor-shuffle merge, so the lowest index wins ties.  The cluster size is the sum of the bins
+// (the same for every subspace): an empty cluster keeps its code, and subspace 0 stores the
+// size to counts[k].  If the histogram arrives as S > 1 partial arrays they are added while
+// loading (integer, exact) and the total is stored to hist.
 // ---------------------------------------------------------------------------------------------
-constexpr int VOTE_MAX_CW = 1024;        // clusters per workgroup (parking space: 8 KB of LDS)
+constexpr int VOTE_MAX_CW = 1024;        // clusters per workgroup
+constexpr int VOTE_THREADS = 1024;       // 16 waves: many row reads in flight
+constexpr int VOTE_WAVES = VOTE_THREADS / 64;
+constexpr int VOTE_CPW = 2;              // clusters per wave whose sums are held in registers together
 
-__global__ __launch_bounds__(1024) void vote_kernel(uint32_t* __restrict__ hist, const uint32_t* __restrict__ parts,
-                                                    int S, size_t part_stride, uint32_t* __restrict__ counts,
-                                                    int K, int M, int CW, const float* __restrict__ tables,
-                                                    uint8_t* __restrict__ centers)
+__global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict__ hist,
+                                                            const uint32_t* __restrict__ parts, int S,
+                                                            size_t part_stride, uint32_t* __restrict__ counts,
+                                                            int K, int M, int CW, const float* __restrict__ tables,
+                                                            uint8_t* __restrict__ centers)
 {
-    __shared__ float4 At[L * 128 / 4];          // [j][128 candidates]
-    __shared__ float pv[VOTE_MAX_CW];           // first half: best value per cluster
-    __shared__ int pi[VOTE_MAX_CW];             // first half: its candidate
-    __shared__ float lst_h[16][L];              // per wave: counts of the non-zero bins, ascending j
-    __shared__ uint8_t lst_j[16][L];            // per wave: their bin indices
+    constexpr int NF = 8192 / VOTE_THREADS;     // float4 per thread per half of the table
+    __shared__ float4 At[128 * 64];             // [row j of the half][lane: candidates 4 lane .. 4 lane + 3]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int blocks_per_m = (K + CW - 1) / CW;
     const int m = blockIdx.x / blocks_per_m;
     const int c0 = (blockIdx.x % blocks_per_m) * CW;
     const int cn = (K - c0 < CW) ? K - c0 : CW;
-    const float* A = tables + (size_t)m * L * L;
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes below this one
-    const float2* At2 = reinterpret_cast<const float2*>(At);
+    const v4f* A4v = reinterpret_cast<const v4f*>(tables + (size_t)m * L * L);        // row j = A4v[64 j .. 64 j + 63]
+    v4f* Atv = reinterpret_cast<v4f*>(At);
 
-    for (int half = 0; half < 2; ++half) {
-        __syncthreads();                        // the previous half is no longer being read
+    // bins chunk*64 + lane, chunk = 0..3, of one (cluster, subspace): the S <= 16 partial arrays are added, all
+    // loads of a cluster in flight together (slices past S re-read the last one and are not added)
+    auto load_bins = [&](size_t pair, uint32_t (&out)[4]) {
+        const size_t at = pair * L + lane;
+        if (S <= 1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int f = i * 1024 + tid;             // float4 index in the half table: row j = f / 32, column quad f % 32
-            At[f] = *reinterpret_cast<const float4*>(A + (size_t)(f >> 5) * L + half * 128 + (f & 31) * 4);
+            for (int chunk = 0; chunk < 4; ++chunk) out[chunk] = hist[at + chunk * 64];
+            return;
         }
-        __syncthreads();
-        for (int c = wave; c < cn; c += 16) {
-            const int k = c0 + c;
-            const size_t pair = (size_t)k * M + m;
-            uint32_t hv[4];
-            if (S > 1 && half == 0) {
+        uint32_t t[8][4];
 #pragma unroll
-                for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = 0u;
-                for (int sl = 0; sl < S; ++sl) {
-                    const uint32_t* h = parts + (size_t)sl * part_stride + pair * L;
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t* src = parts + (size_t)(u < S ? u : S - 1) * part_stride + at;
 #pragma unroll
-                    for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] += h[chunk * 64 + lane];
-                }
+            for (int chunk = 0; chunk < 4; ++chunk) t[u][chunk] = src[chunk * 64];
+        }
 #pragma unroll
-                for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[chunk];
-            } else {
-                // (second half with S > 1: each lane reads back the totals it stored itself)
-                const uint32_t* h = hist + pair * L;
+        for (int chunk = 0; chunk < 4; ++chunk) {
+            uint32_t sum = 0u;
 #pragma unroll
-                for (int chunk = 0; chunk < 4; ++chunk) hv[chunk] = h[chunk * 64 + lane];
+            for (int u = 0; u < 8; ++u) sum += (u < S) ? t[u][chunk] : 0u;
+            out[chunk] = sum;
+        }
+        if (S > 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t* src = parts + (size_t)(8 + u < S ? 8 + u : S - 1) * part_stride + at;
+#pragma unroll
+                for (int chunk = 0; chunk < 4; ++chunk) t[u][chunk] = src[chunk * 64];
             }
-            // compact the non-zero bins (ascending j) into this wave's list; their number is wave-uniform
-            int nnz = 0;
 #pragma unroll
             for (int chunk = 0; chunk < 4; ++chunk) {
-                const uint64_t mask = __ballot(hv[chunk] != 0u);
-                if (hv[chunk] != 0u) {
-                    const int pos = nnz + __popcll(mask & lt_mask);
-                    lst_h[wave][pos] = (float)hv[chunk];
-                    lst_j[wave][pos] = (uint8_t)(chunk * 64 + lane);
-                }
-                nnz += __popcll(mask);
+                uint32_t sum = 0u;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += (8 + u < S) ? t[u][chunk] : 0u;
+                out[chunk] += sum;
             }
-            uint32_t cnt = hv[0] + hv[1] + hv[2] + hv[3];
+        }
+    };
+    auto fma_row = [](float4& acc, float h, const float4 r) {
+        acc.x = fmaf(h, r.x, acc.x); acc.y = fmaf(h, r.y, acc.y);
+        acc.z = fmaf(h, r.z, acc.z); acc.w = fmaf(h, r.w, acc.w);
+    };
+
+    for (int b0 = 0; b0 < cn; b0 += VOTE_WAVES * VOTE_CPW) {
+        v4f pf[NF];
+#pragma unroll
+        for (int i = 0; i < NF; ++i) pf[i] = A4v[i * VOTE_THREADS + tid];                  // rows 0 .. 127
+        uint32_t hv[VOTE_CPW][4];
+        float4 v[VOTE_CPW];
+#pragma unroll
+        for (int q = 0; q < VOTE_CPW; ++q) {
+            const int c = b0 + q * VOTE_WAVES + wave;
+            v[q] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (c < cn) {
+                load_bins((size_t)(c0 + c) * M + m, hv[q]);
+            } else {
+#pragma unroll
+                for (int chunk = 0; chunk < 4; ++chunk) hv[q][chunk] = 0u;
+            }
+        }
+        // one half of the bins: fill the LDS rows from the registers, start the next half's loads, walk
+        auto run_half = [&](auto half_c) {
+            constexpr int half = decltype(half_c)::value;
+            __syncthreads();                    // the rows in LDS are no longer being read
+#pragma unroll
+            for (int i = 0; i < NF; ++i) Atv[i * VOTE_THREADS + tid] = pf[i];
+            __syncthreads();
+            if (half == 0) {
+#pragma unroll
+                for (int i = 0; i < NF; ++i) pf[i] = A4v[8192 + i * VOTE_THREADS + tid];   // rows 128 .. 255
+            }
+#pragma unroll
+            for (int q = 0; q < VOTE_CPW; ++q) {
+#pragma unroll
+                for (int ch = 0; ch < 2; ++ch) {
+                    const uint32_t hb = hv[q][2 * half + ch];
+                    const int hfi = __builtin_bit_cast(int, (float)hb);
+                    uint64_t mask = __ballot(hb != 0u);
+                    const float4* rows = At + ch * 64 * 64 + lane;
+                    float4 acc = v[q];
+                    int n = __popcll(mask);
+                    for (; n >= 8; n -= 8) {                                 // eight rows in flight, fmas in order
+                        int j[8];
+                        float h[8];
+                        float4 r[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            j[u] = __builtin_ctzll(mask);
+                            mask &= mask - 1;
+                            h[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(hfi, j[u]));
+                            r[u] = rows[j[u] * 64];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);                   // all eight reads before the first fmaf
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) fma_row(acc, h[u], r[u]);
+                    }
+                    for (; n > 0; --n) {
+                        const int j = __builtin_ctzll(mask);
+                        mask &= mask - 1;
+                        fma_row(acc, __builtin_bit_cast(float, __builtin_amdgcn_readlane(hfi, j)), rows[j * 64]);
+                    }
+                    v[q] = acc;
+                }
+            }
+        };
+        run_half(std::integral_constant<int, 0>{});
+        run_half(std::integral_constant<int, 1>{});
+#pragma unroll
+        for (int q = 0; q < VOTE_CPW; ++q) {
+            const int c = b0 + q * VOTE_WAVES + wave;
+            if (c >= cn) continue;                                           // the same for the whole wave
+            const size_t pair = (size_t)(c0 + c) * M + m;
+            if (S > 1) {
+#pragma unroll
+                for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[q][chunk];
+            }
+            uint32_t cnt = hv[q][0] + hv[q][1] + hv[q][2] + hv[q][3];
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
-            if (half == 0 && m == 0 && lane == 0) counts[k] = cnt;
-            if (cnt == 0) continue;                                  // empty cluster keeps its code
-            float v0 = 0.0f, v1 = 0.0f;
-            int i = 0;
-            for (; i + 4 <= nnz; i += 4) {                           // rows of four bins in flight, fmas in order
-                const int j0 = lst_j[wave][i], j1 = lst_j[wave][i + 1], j2 = lst_j[wave][i + 2],
-                          j3 = lst_j[wave][i + 3];
-                const float h0 = lst_h[wave][i], h1 = lst_h[wave][i + 1], h2 = lst_h[wave][i + 2],
-                            h3 = lst_h[wave][i + 3];
-                const float2 r0 = At2[j0 * 64 + lane], r1 = At2[j1 * 64 + lane], r2 = At2[j2 * 64 + lane],
-                             r3 = At2[j3 * 64 + lane];
-                v0 = fmaf(h0, r0.x, v0); v1 = fmaf(h0, r0.y, v1);
-                v0 = fmaf(h1, r1.x, v0); v1 = fmaf(h1, r1.y, v1);
-                v0 = fmaf(h2, r2.x, v0); v1 = fmaf(h2, r2.y, v1);
-                v0 = fmaf(h3, r3.x, v0); v1 = fmaf(h3, r3.y, v1);
-            }
-            for (; i < nnz; ++i) {
-                const int j = lst_j[wave][i];
-                const float hf = lst_h[wave][i];
-                const float2 row = At2[j * 64 + lane];
-                v0 = fmaf(hf, row.x, v0);
-                v1 = fmaf(hf, row.y, v1);
-            }
-            float b = INFINITY;
-            int bi = IDX_NONE;
-            if (v0 < b) { b = v0; bi = half * 128 + lane * 2; }
-            if (v1 < b) { b = v1; bi = half * 128 + lane * 2 + 1; }
+            if (m == 0 && lane == 0) counts[c0 + c] = cnt;
+            if (cnt == 0) continue;                                          // empty cluster keeps its code
+            float b = v[q].x;
+            int bi = lane * 4;
+            if (v[q].y < b) { b = v[q].y; bi = lane * 4 + 1; }
+            if (v[q].z < b) { b = v[q].z; bi = lane * 4 + 2; }
+            if (v[q].w < b) { b = v[q].w; bi = lane * 4 + 3; }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) {
-                float ob = __shfl_xor(b, d);
-                int oi = __shfl_xor(bi, d);
+                const float ob = __shfl_xor(b, d);
+                const int oi = __shfl_xor(bi, d);
                 if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
             }
-            if (lane == 0) {
-                if (half == 0) {
-                    pv[c] = b;
-                    pi[c] = bi;
-                } else {
-                    float fb = pv[c];
-                    int fi = pi[c];
-                    if (b < fb) { fb = b; fi = bi; }
-                    centers[pair] = (uint8_t)((fi == IDX_NONE) ? 0 : fi);
-                }
-            }
+            if (lane == 0) centers[pair] = (uint8_t)bi;
         }
     }
 }
