@@ -213,13 +213,52 @@ void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* i
                    int32_t* assign, float* dist, hipStream_t st);
 
 // M = 4 scans over regrouped codes: variants 70..79
+// Codes per lane-slot R of the 512-thread half-plane scan (a workgroup takes 128 R codes, one workgroup per
+// compute unit at a time).  The time of a launch is about rounds * (R + 7) with rounds = ceil(workgroups / CUs):
+// R codes' reads per tile plus a fill and two barriers worth about 7.  Below a few rounds the rounding decides:
+// 1.1e6 codes are 269 workgroups at R = 32, two rounds, but 430 at R = 20, two rounds of 5/8 the length.
+int scan4p_codes_per_slot(int64_t n_alloc)
+{
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        ncu = v;
+    }
+    static const int cand[] = {32, 31, 28, 24, 20, 16};
+    int best = 32;
+    int64_t best_cost = INT64_MAX;
+    for (int R : cand) {
+        const int64_t wgs = (n_alloc + 128 * R - 1) / (128 * R);
+        const int64_t cost = ((wgs + ncu - 1) / ncu) * (R + 7);
+        if (cost < best_cost) { best_cost = cost; best = R; }
+    }
+    return best;
+}
+
 void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
                          int ntiles, int32_t* assign, float* dist, hipStream_t st)
 {
+    int R = 0;
     switch (variant) {
-        case 71: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;   // 70
+        case 70: R = scan4p_codes_per_slot(n_alloc); break;
+        case 71: R = 28; break;
+        case 72: R = 31; break;
+        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); return;
+        case 74: R = 24; break;
+        case 75: R = 20; break;
+        case 76: R = 16; break;
+        default: R = 32; break;      // 77..79
+    }
+    switch (R) {
+        case 16: launch_scan4p<16, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 20: launch_scan4p<20, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 24: launch_scan4p<24, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 28: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 31: launch_scan4p<31, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
     }
 }
 

@@ -996,8 +996,8 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
     // position q that attains it in that tile the 8 sums of its centers are rebuilt from the tile image in global
     // memory (same bits, same sum order) and the lowest center index with that sum is kept.  Almost always there
     // is one such q; the loop over them only repeats on exact ties between lane positions.
-    static_assert(R % 4 == 0 && R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
-    constexpr int CPL = R / 4;                      // codes per lane in the epilogue
+    static_assert(R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+    constexpr int CPL = (R + 3) / 4;                // codes per lane in the epilogue (the last ones may be past C)
     constexpr int EB = THREADS > 768 ? 2 : 4;       // codes whose image reads are in flight together
     __syncthreads();                                // every wave is done with the last tile
     {
@@ -1028,7 +1028,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
             if (i0 + e >= CPL) { cand[e] = 0u; og[e] = ORIGIN_NONE; pk[e] = 0u; smin[e] = 0.f; tmin[e] = 0; bi[e] = IDX_NONE; continue; }
             const int j = (i0 + e) * THREADS + tid;
             int64_t n = base + j;
-            const bool live = n < N;
+            const bool live = n < N && j < C;
             if (!live) n = N - 1;
             const float4 ra = lds_read16(tb, (uint32_t)j * 32u), rb = lds_read16(tb, (uint32_t)j * 32u + 16u);
             const float b0 = ra.x, b1 = ra.z, b2 = rb.x, b3 = rb.z;
