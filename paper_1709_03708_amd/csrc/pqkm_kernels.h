@@ -367,6 +367,22 @@ __global__ __launch_bounds__(THREADS) void assign_scan_kernel(const uint8_t* __r
 //  * the next tile is prefetched from global memory into registers while the current one is
 //    being scanned, so only the LDS write of the fill is exposed between two barriers.
 // ---------------------------------------------------------------------------------------------
+// Field unpacks that issue at the full VALU rate.  Measured on this chip: v_and_b32, v_lshrrev_b32, v_add_u32
+// and the fp32 add / mul / fma issue every 2.4 clocks per SIMD; v_lshlrev_b32 (also as SDWA), v_min/max/min3,
+// v_bfe_u32 and the other three-operand integer forms every 4.2.  A register holds a 15-bit byte offset in its low
+// bits and a 17-bit byte offset from bit 15 up.
+__device__ __forceinline__ uint32_t unpack_low15(uint32_t mask7fff, uint32_t v)
+{
+    uint32_t r;
+    asm volatile("v_and_b32 %0, %1, %2" : "=v"(r) : "s"(mask7fff), "v"(v));
+    return r;
+}
+__device__ __forceinline__ uint32_t unpack_high17(uint32_t v)
+{
+    uint32_t r;
+    asm volatile("v_lshrrev_b32 %0, 15, %1" : "=v"(r) : "v"(v));
+    return r;
+}
 __device__ __forceinline__ uint32_t sdwa_shl_word0(uint32_t sh, uint32_t v)
 {
     uint32_t r;
@@ -896,10 +912,11 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
     const int q = tid % LPS;
     const int c = tid / LPS;
     const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
+    const uint32_t low15 = 0x7fffu;
 
-    // per code two registers of 16-bit fields: (byte offset of the lane's piece in plane (m, 0)) / 16, where the
-    // planes of m = 2, 3 are addressed from 64 KB up so that every remaining plane offset fits the DS immediate
+    // per code two registers, each a 15-bit and a 17-bit field: the byte offset of the lane's piece in its row
+    // (subspaces 0 and 1, low fields) and the same plus 64 KB (subspaces 2 and 3, high fields), so that every
+    // remaining plane offset (0 to 3 planes of 16 KB) fits the DS immediate and each unpack is one full-rate op
     uint32_t pa[R], pb[R];
     float best[R];
     int tix[R];
@@ -908,12 +925,12 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
         int64_t n = base + (int64_t)r * SLOTS + c;
         if (n >= N) n = N - 1;
         uint32_t pk = gco ? gco[n].x : *reinterpret_cast<const uint32_t*>(codes + n * 4);
-        uint32_t f0 = ((pk & 255u) << 2) | (uint32_t)q;
-        uint32_t f1 = (((pk >> 8) & 255u) << 2) | (uint32_t)q;
-        uint32_t f2 = ((((pk >> 16) & 255u) << 2) | (uint32_t)q) + 4096u;
-        uint32_t f3 = (((pk >> 24) << 2) | (uint32_t)q) + 4096u;
-        pa[r] = f0 | (f1 << 16);
-        pb[r] = f2 | (f3 << 16);
+        uint32_t f0 = ((pk & 255u) << 6) | ((uint32_t)q << 4);
+        uint32_t f1 = (((pk >> 8) & 255u) << 6) | ((uint32_t)q << 4);
+        uint32_t f2 = ((((pk >> 16) & 255u) << 6) | ((uint32_t)q << 4)) + 65536u;
+        uint32_t f3 = (((pk >> 24) << 6) | ((uint32_t)q << 4)) + 65536u;
+        pa[r] = f0 | (f2 << 15);
+        pb[r] = f1 | (f3 << 15);
         best[r] = INFINITY;
         tix[r] = -1;
     }
@@ -935,10 +952,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
     struct Pair { float4 a, b; };
     auto issue = [&](int step) -> Pair {
         const int r = step / 4, m = step % 4;
-        uint32_t ad = (m == 0) ? sdwa_shl_word0(four, pa[r])
-                    : (m == 1) ? sdwa_shl_word1(four, pa[r])
-                    : (m == 2) ? sdwa_shl_word0(four, pb[r])
-                               : sdwa_shl_word1(four, pb[r]);
+        uint32_t ad = (m == 0) ? unpack_low15(low15, pa[r])
+                    : (m == 1) ? unpack_low15(low15, pb[r])
+                    : (m == 2) ? unpack_high17(pa[r])
+                               : unpack_high17(pb[r]);
         const uint32_t po = (m & 1) ? 2 * HPLANE : 0;
         Pair p;
         p.a = lds_read16(tb, ad + po);
@@ -1342,10 +1359,11 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
     const int q = tid % LPS;
     const int c = tid / LPS;
     const int64_t base = (int64_t)blockIdx.x * C;
-    const uint32_t four = 4;
+    const uint32_t low15 = 0x7fffu;
 
-    // per code four registers of 16-bit fields (x_m*64 + 16q)/16, the planes of m >= 4 addressed from 64 KB up so
-    // that every remaining plane offset fits the DS immediate
+    // per code four registers, register j a 15-bit field (byte offset x_j*64 + 16q of subspace j's piece in its
+    // row) and a 17-bit field from bit 15 up (the same for subspace j + 4, plus 64 KB), so that every remaining
+    // plane offset (0 to 3 planes of 16 KB) fits the DS immediate and each unpack is one full-rate instruction
     uint32_t fld[R][4];
     float best[R];
     int tix[R];
@@ -1365,10 +1383,8 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
         }
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const uint32_t src = w < 2 ? lo : hi;
-            const uint32_t xa = (src >> (16 * (w & 1))) & 255u, xb = (src >> (16 * (w & 1) + 8)) & 255u;
-            const uint32_t up = w < 2 ? 0u : 4096u;
-            fld[r][w] = (((xa << 2) | (uint32_t)q) + up) | ((((xb << 2) | (uint32_t)q) + up) << 16);
+            const uint32_t xa = (lo >> (8 * w)) & 255u, xb = (hi >> (8 * w)) & 255u;
+            fld[r][w] = ((xa << 6) | ((uint32_t)q << 4)) | ((((xb << 6) | ((uint32_t)q << 4)) + 65536u) << 15);
         }
         best[r] = INFINITY;
         tix[r] = -1;
@@ -1387,7 +1403,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
 
     auto issue = [&](int step) -> float4 {
         const int r = step / M, m = step % M;
-        const uint32_t ad = (m & 1) ? sdwa_shl_word1(four, fld[r][m / 2]) : sdwa_shl_word0(four, fld[r][m / 2]);
+        const uint32_t ad = (m < 4) ? unpack_low15(low15, fld[r][m]) : unpack_high17(fld[r][m - 4]);
         return lds_read16(tb, ad + (uint32_t)(m & 3) * PLANE);
     };
 
