@@ -568,9 +568,8 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
 template <int DS>
 void launch_encode(const float* vectors, int64_t N, int M, const float* codewords, uint8_t* codes, hipStream_t st)
 {
-    constexpr int TH = DS >= 64 ? 512 : 256;
-    hipLaunchKernelGGL((encode_kernel<DS, TH>), dim3((unsigned)((N + TH - 1) / TH), (unsigned)M), dim3(TH),
-                       (size_t)L * DS * sizeof(float), st, vectors, N, M, codewords, codes);
+    hipLaunchKernelGGL((encode_kernel<DS, 256>), dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, st,
+                       vectors, N, M, codewords, codes);
 }
 
 }  // namespace

@@ -45,24 +45,22 @@ __global__ __launch_bounds__(256) void build_tables_kernel(const float* __restri
 // fp32, ascending dimension, one subtraction and one fused multiply-add per dimension (explicit
 // fmaf; the file is compiled without contraction); ties go to the lowest index (strict "<" over
 // ascending l).  Grid (blocks of THREADS vectors, M), one thread per vector: the subvector sits in
-// registers, the 256 codewords of the subspace in LDS (read as wave-uniform broadcasts, four
-// codewords in flight for instruction-level parallelism; long subvectors use 512 threads so that
-// every SIMD has two waves to alternate between).  Plain VALU work, 3 flops per
-// (vector, codeword, dimension); an MFMA formulation through ||x||^2 - 2 x.c + ||c||^2 would round
-// differently and could not be compared bit for bit.
+// registers; the codewords are the same for every lane, so the scalar unit fetches them (s_load
+// through the constant cache) and each subtraction takes one as its scalar source: no LDS, no
+// vector loads in the loop; four codewords in flight for instruction-level parallelism.  Plain
+// VALU work, 3 flops per (vector, codeword, dimension); an MFMA formulation through
+// ||x||^2 - 2 x.c + ||c||^2 would round differently and could not be compared bit for bit.
 // ---------------------------------------------------------------------------------------------
 template <int DS, int THREADS>
 __global__ __launch_bounds__(THREADS) void encode_kernel(const float* __restrict__ vectors, int64_t N, int M,
-                                                     const float* __restrict__ codewords,
-                                                     uint8_t* __restrict__ codes)
+                                                           const float* __restrict__ codewords,
+                                                           uint8_t* __restrict__ codes)
 {
-    extern __shared__ float cw[];                          // [256][DS]
     const int m = blockIdx.y;
-    const float* src = codewords + (size_t)m * L * DS;
-    for (int i = threadIdx.x; i < L * DS; i += THREADS) cw[i] = src[i];
-    __syncthreads();
-    const int64_t n = (int64_t)blockIdx.x * THREADS + threadIdx.x;
-    if (n >= N) return;
+    const float* __restrict__ cw = codewords + (size_t)m * L * DS;      // uniform
+    int64_t n = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+    const bool live = n < N;
+    if (!live) n = N - 1;
     float x[DS];
     const float* xv = vectors + ((size_t)n * M + m) * DS;
 #pragma unroll
@@ -86,7 +84,7 @@ __global__ __launch_bounds__(THREADS) void encode_kernel(const float* __restrict
                 bl = l0 + u;
             }
     }
-    codes[n * M + m] = (uint8_t)bl;
+    if (live) codes[n * M + m] = (uint8_t)bl;
 }
 
 // any subvector length: same arithmetic, operands read through the caches
