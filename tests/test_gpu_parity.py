@@ -275,6 +275,39 @@ def _update_case(env, rng, M, K, N):
         np.testing.assert_array_equal(d_cent2.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_assign_then_update(env, seed):
+    """Seeded random shapes, value mixes (uniform, skewed residues, few distinct subcodes) and tables (real and
+    integer, i.e. many exact ties): assignment, distances, histogram, counts and new centers, all bit for bit."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        M = int(rng.choice([4, 4, 4, 8, 8, 16, 32]))
+        N = int(rng.integers(1, 300_000)) if M <= 8 else int(rng.integers(1, 40_000))
+        K = int(rng.integers(1, 1200))
+        kind = ("uniform", "skew", "few")[int(rng.integers(0, 3))]
+        if kind == "uniform":
+            codes = rng.integers(0, 256, (N, M), dtype=np.uint8)
+        elif kind == "skew":
+            codes = (rng.integers(0, 256, (N, M)) * rng.integers(0, 2, (N, M)) | rng.integers(0, 4, (N, 1))).astype(np.uint8)
+        else:
+            codes = rng.integers(0, 5, (N, M), dtype=np.uint8)
+        centers = codes[rng.integers(0, N, K)].copy()
+        tables = rand_tables(rng, M, integer=bool(rng.integers(0, 2)))
+        progress(f"random case seed={seed} #{case}: M={M} N={N} K={K} {kind}")
+        a, d = pq.assign(_dev(env, codes), _dev(env, centers), _dev(env, tables))
+        d_cent = _dev(env, centers)
+        _, hist, counts = pq.update(_dev(env, codes), a, _dev(env, tables), d_cent)
+        _sync(env)
+        ra, rd = oracle.assign(codes, centers, tables)
+        rc, rh, rcnt = oracle.update(codes, ra, tables, centers)
+        np.testing.assert_array_equal(a.cpu().numpy(), ra)
+        np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
 def test_update_empty_input_and_big_counts(env):
     pq, oracle, torch, dev = env["pq"], env["oracle"], env["torch"], env["dev"]
     rng = np.random.default_rng(9)
