@@ -1348,7 +1348,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
     constexpr int NF = TILE_F4 / THREADS;
     constexpr uint32_t PLANE = 16384;       // bytes per subspace plane: 256 subcodes x 16 centers
     static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
-    static_assert(R % 4 == 0 && R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+    static_assert(R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
 
     __shared__ float4 tile[TILE_F4];
     const char* tb = reinterpret_cast<const char*>(tile);
@@ -1441,7 +1441,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
     }
 
     // Epilogue, transposed through LDS as in assign_scan4p_kernel: lane l finishes the codes l, l + THREADS, ...
-    constexpr int CPL = R / 4;
+    constexpr int CPL = (R + 3) / 4;                // codes per lane (the last ones may be past C)
     __syncthreads();
     {
         float2* rec = reinterpret_cast<float2*>(tile);
@@ -1457,7 +1457,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
     for (int i0 = 0; i0 < CPL; ++i0) {
         const int j = i0 * THREADS + tid;
         int64_t n = base + j;
-        const bool live = n < N;
+        const bool live = n < N && j < C;
         if (!live) n = N - 1;
         const float4 ra = lds_read16(tb, (uint32_t)j * 32u), rb = lds_read16(tb, (uint32_t)j * 32u + 16u);
         const float b0 = ra.x, b1 = ra.z, b2 = rb.x, b3 = rb.z;

@@ -132,7 +132,7 @@ def test_assign_regrouped_scan(env, variant, kind, N):
         _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73])
+@pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73, 74, 75, 76, 77, 78])
 @pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 300007), ("uniform", 4093), ("uniform", 3),
                                     ("one_class", 5000), ("latin", 8192)])
 def test_assign_regrouped_scan_64bit_codes(env, variant, kind, N):
