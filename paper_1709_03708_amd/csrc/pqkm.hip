@@ -443,7 +443,9 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
     const bool grouped = variant_grouped(M, variant);
     int64_t per_launch = opt.launch_codes;
-    if (grouped && per_launch > GROUP_CHUNK_MAX) per_launch = GROUP_CHUNK_MAX;
+    // a little below the limit: with its padding a launch of exactly 2^26 codes needs one workgroup more than
+    // 64 full rounds of 4096-code workgroups, and that workgroup would run a round of its own
+    if (grouped && per_launch > GROUP_CHUNK_MAX - 16384) per_launch = GROUP_CHUNK_MAX - 16384;
     const float4* rows = reinterpret_cast<const float4*>(ws + c.rows_off);
     uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
