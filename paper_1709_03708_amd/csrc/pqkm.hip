@@ -213,20 +213,26 @@ void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* i
                    int32_t* assign, float* dist, hipStream_t st);
 
 // M = 4 scans over regrouped codes: variants 70..79
+// compute units of the current device (asked once; 256 if the query fails)
+int cu_count()
+{
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
 // Codes per lane-slot R of the 512-thread half-plane scan (a workgroup takes 128 R codes, one workgroup per
 // compute unit at a time).  The time of a launch is about rounds * (R + 7) with rounds = ceil(workgroups / CUs):
 // R codes' reads per tile plus a fill and two barriers worth about 7.  Below a few rounds the rounding decides:
 // 1.1e6 codes are 269 workgroups at R = 32, two rounds, but 430 at R = 20, two rounds of 5/8 the length.
 int scan4p_codes_per_slot(int64_t n_alloc)
 {
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-            v = 256;
-        ncu = v;
-    }
+    const int ncu = cu_count();
     static const int cand[] = {32, 31, 28, 24, 20, 16};
     int best = 32;
     int64_t best_cost = INT64_MAX;
@@ -267,14 +273,7 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
 // R = 24, 10 rounds of 2500 at R = 25, measured 12.2 ms against 11.4 ms at K = 4000).
 int scan8p_codes_per_slot(int64_t n_alloc)
 {
-    static int ncu = 0;
-    if (ncu == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-            v = 256;
-        ncu = v;
-    }
+    const int ncu = cu_count();
     static const int cand[] = {25, 24, 22, 20, 18, 16};
     int best = 24;
     int64_t best_cost = INT64_MAX;
