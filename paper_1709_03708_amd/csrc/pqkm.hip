@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -24,7 +25,7 @@ struct Options {
 };
 Options g_opt;
 std::mutex g_mu;
-int g_hist_groups = 64;    // target number of cluster groups of the LDS-privatised histogram (measured best)
+std::atomic<int> g_hist_groups{64};    // target number of cluster groups of the LDS-privatised histogram (measured best)
 
 struct EventPair { hipEvent_t a, b; };
 std::vector<EventPair> g_pool;      // all events ever created
@@ -51,7 +52,8 @@ HistPlan hist_plan(int64_t N, int M, int K)
     const int kt_max = (HIST_LDS_WORDS / L) / M;           // 128 KB of LDS / (M KB per cluster)
     if (kt_max < 1) return p;
     // about g_hist_groups groups (a byte names at most 255), within the LDS budget
-    int kt = (K + g_hist_groups - 1) / g_hist_groups;
+    const int hg = g_hist_groups.load();
+    int kt = (K + hg - 1) / hg;
     if (kt > kt_max) kt = kt_max;
     p.KT = kt;
     p.groups = ((int64_t)K + p.KT - 1) / p.KT;
