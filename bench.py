@@ -108,6 +108,57 @@ def naive_update_bench(args, w, pq, torch, dev) -> int:
     return 0
 
 
+def microbench(torch) -> int:
+    """The microbenchmarks behind the roofline denominators (paper_1709_03708_amd/csrc/microbench.hip): LDS read
+    and write rates, VALU issue rates, the scan's instruction mix with and without a tile switch.  Prints a table
+    on stderr and one JSON line on stdout."""
+    import ctypes
+    import os
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_1709_03708_amd", "libpqkm_microbench.so")
+    if not os.path.exists(path):
+        print("bench.py: " + path + " is missing (run __graft_entry__.build())", file=sys.stderr)
+        return 2
+    lib = ctypes.CDLL(path)
+    lib.pqkm_microbench.restype = ctypes.c_int
+    lib.pqkm_microbench.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+    torch.zeros(1, device="cuda:0")                      # device and context
+    clock = 2.4e9
+    tests = [(0, "ds_read_b128, lane-consecutive", "lds"), (1, "ds_read_b64, lane-consecutive", "lds"),
+             (2, "ds_read_b32, lane-consecutive", "lds"), (5, "ds_read_b128, 8 lanes per 128-byte row, random rows", "lds"),
+             (3, "ds_read_b128, 4 lanes per 64-byte row, random rows", "lds"),
+             (6, "ds_read_b128, 2 lanes per 32-byte row, random rows", "lds"),
+             (7, "ds_read_b128, 1 lane per 16-byte row, random rows", "lds"),
+             (4, "ds_write_b128, 128 KB per iteration", "lds"),
+             (10, "v_add_f32", "valu"), (11, "v_min_f32", "valu"), (12, "v_min3_f32", "valu"),
+             (13, "v_lshlrev_b32 (SDWA)", "valu"), (14, "v_and_b32", "valu"), (15, "v_lshrrev_b32", "valu"),
+             (16, "v_fma_f32", "valu"),
+             (20, "scan mix, 31 codes per lane-slot", "mix"), (21, "scan mix + two barriers per tile", "mix"),
+             (22, "scan mix + two barriers + 128 KB written per tile", "mix")]
+    out = {}
+    for what, name, kind in tests:
+        ms, units = ctypes.c_float(0), ctypes.c_double(0)
+        if lib.pqkm_microbench(what, ctypes.byref(ms), ctypes.byref(units)) != 0:
+            print(f"bench.py: microbenchmark {what} failed", file=sys.stderr)
+            return 1
+        clocks = ms.value * 1e-3 * clock
+        if kind == "lds":
+            v = units.value / clocks
+            line = f"{v:7.1f} B/clk/CU"
+        elif kind == "valu":
+            v = clocks / units.value
+            line = f"{v:7.2f} clocks per wave64 instruction per SIMD"
+        else:
+            v = units.value * 4.0 / clocks
+            line = f"{100 * v:7.1f} % of the LDS read peak ({clocks / 400:.0f} clocks per tile)"
+        out[name] = v
+        print(f"{name:52s} {ms.value:8.3f} ms  {line}", file=sys.stderr)
+    print(json.dumps({"microbench": out, "clock_hz": clock,
+                      "units": {"lds": "B/clk/CU", "valu": "clocks per wave64 instruction per SIMD",
+                                "mix": "fraction of 256 B/clk/CU"}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +172,9 @@ def main() -> int:
     ap.add_argument("--naive-update", action="store_true",
                     help="time the sparse-voting update (Eq. 7-8) against the naive update (Eq. 6) on the "
                          "configuration's first assignment, as in the paper's per-step runtime table; prints its own line")
+    ap.add_argument("--microbench", action="store_true",
+                    help="run the microbenchmarks behind the roofline denominators (LDS read and write rates, VALU "
+                         "issue rates, the scan's instruction mix with and without a tile switch) and print them")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of 1 GiB (5 times): the known-size kernel against which "
                          "the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc are scaled")
@@ -140,6 +194,8 @@ def main() -> int:
         return 2
     pq.load()                                           # fails loudly if the HIP library is missing
     dev = torch.device("cuda:0")
+    if args.microbench:
+        return microbench(torch)
     if args.copy_calibration:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)

@@ -106,3 +106,16 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libpqkm.so")
     with pytest.raises(ImportError):
         b.load()
+
+
+def test_microbenchmark_library_loads_and_rejects_bad_arguments():
+    """The measurement library behind `bench.py --microbench` (not part of the method): it loads, exports its one
+    entry point, and refuses null outputs before touching a device."""
+    from paper_1709_03708_amd import build
+
+    if not os.path.exists(build.MICROBENCH_LIB):
+        build.build()
+    mb = ctypes.CDLL(build.MICROBENCH_LIB)
+    mb.pqkm_microbench.restype = ctypes.c_int
+    mb.pqkm_microbench.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+    assert mb.pqkm_microbench(0, None, None) == 1
