@@ -134,7 +134,8 @@ def microbench(torch) -> int:
              (13, "v_lshlrev_b32 (SDWA)", "valu"), (14, "v_and_b32", "valu"), (15, "v_lshrrev_b32", "valu"),
              (16, "v_fma_f32", "valu"),
              (20, "scan mix, 31 codes per lane-slot", "mix"), (21, "scan mix + two barriers per tile", "mix"),
-             (22, "scan mix + two barriers + 128 KB written per tile", "mix")]
+             (22, "scan mix + two barriers + 128 KB written per tile", "mix"),
+             (30, "streaming copy of 1 GiB (HBM read + write)", "hbm")]
     out = {}
     for what, name, kind in tests:
         ms, units = ctypes.c_float(0), ctypes.c_double(0)
@@ -148,6 +149,9 @@ def microbench(torch) -> int:
         elif kind == "valu":
             v = clocks / units.value
             line = f"{v:7.2f} clocks per wave64 instruction per SIMD"
+        elif kind == "hbm":
+            v = units.value * torch.cuda.get_device_properties(0).multi_processor_count / (ms.value * 1e-3) / 1e12
+            line = f"{v:7.2f} TB/s"
         else:
             v = units.value * 4.0 / clocks
             line = f"{100 * v:7.1f} % of the LDS read peak ({clocks / 400:.0f} clocks per tile)"
@@ -155,7 +159,7 @@ def microbench(torch) -> int:
         print(f"{name:52s} {ms.value:8.3f} ms  {line}", file=sys.stderr)
     print(json.dumps({"microbench": out, "clock_hz": clock,
                       "units": {"lds": "B/clk/CU", "valu": "clocks per wave64 instruction per SIMD",
-                                "mix": "fraction of 256 B/clk/CU"}}))
+                                "mix": "fraction of 256 B/clk/CU", "hbm": "TB/s"}}))
     return 0
 
 

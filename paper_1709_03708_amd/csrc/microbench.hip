@@ -225,6 +225,12 @@ __global__ __launch_bounds__(512) void scan_mix_kernel(int tiles, float* out, in
     if (s == 12345.678f) out[tid] = s + ti;
 }
 
+// streaming copy of float4 elements (HBM read + write)
+__global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 template <typename F>
 int timed(F launch, float* ms_out)
 {
@@ -257,6 +263,7 @@ extern "C" {
 //   4     ds_write_b128, 128 KB per iteration
 //   10..16 VALU: v_add_f32, v_min_f32, v_min3_f32, v_lshlrev_b32 (SDWA), v_and_b32, v_lshrrev_b32, v_fma_f32
 //   20..22 scan mix, 31 codes per lane-slot: alone / two barriers per tile / barriers and 128 KB written per tile
+//   30    streaming copy of 1 GiB (units: bytes read + written per compute unit)
 // Returns 0, or 1 on an unknown test or a HIP error.  Allocates and frees a small device buffer.
 int pqkm_microbench(int what, float* ms_out, double* units_out)
 {
@@ -321,6 +328,18 @@ int pqkm_microbench(int what, float* ms_out, double* units_out)
             rc = timed([&] { hipLaunchKernelGGL((scan_mix_kernel<31, 2>), dim3(cus), dim3(512), 0, 0, tiles, out, 17); }, ms_out);
             *units_out = 8.0 * 31 * 8 * tiles;
             break;
+        case 30: {
+            const size_t bytes = (size_t)1 << 30;
+            float4 *src = nullptr, *dst = nullptr;
+            if (hipMalloc(&src, bytes) == hipSuccess && hipMalloc(&dst, bytes) == hipSuccess &&
+                hipMemset(src, 0, bytes) == hipSuccess) {
+                rc = timed([&] { hipLaunchKernelGGL(copy_kernel, dim3(cus * 32), dim3(256), 0, 0, src, dst, bytes / 16); }, ms_out);
+                *units_out = 2.0 * (double)bytes / cus;
+            }
+            hipFree(src);
+            hipFree(dst);
+            break;
+        }
         default: rc = 1;
     }
     hipFree(out);
