@@ -15,7 +15,13 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work on `stream` and return; they never synchronise
  *     and allocate or free nothing.  Results are valid once `stream` reaches
- *     the end of the enqueued work.
+ *     the end of the enqueued work.  (pqkm_fit_until is the exception: it
+ *     reads a few counters back per iteration and waits for them.)  The
+ *     enqueued work is kernels only -- no memset or copy nodes -- so a caller
+ *     may capture pqkm_build_tables, pqkm_encode, pqkm_decode, pqkm_assign,
+ *     pqkm_update, pqkm_update_naive and pqkm_fit in a HIP graph (with the
+ *     "profile" option off) and replay it; the workspace need not keep its
+ *     contents between replays.
  *   - `workspace` is device scratch of at least
  *     pqkm_workspace_bytes(N, M, K) bytes, 256-byte aligned, used only during
  *     the call's enqueued work (tile images of the centers, for M = 4 a
