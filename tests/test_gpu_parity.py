@@ -4,6 +4,7 @@ Bar: bit-exact for assignments, minimum distances (given identical fp32 tables),
 counts and updated centers; the tables themselves within 1e-6 relative.
 """
 import dataclasses
+import os
 
 import numpy as np
 import pytest
@@ -419,12 +420,12 @@ def test_fit_until_matches_oracle(env, cfg, over):
     assert s3 == [] and (d3.cpu().numpy() == cent0).all()
 
 
-def _run_config_sampled(env, cfg, n_sample, iters=1):
+def _run_config_sampled(env, cfg, n_sample, iters=1, **over):
     """Full-size run in the launch configuration the benchmark uses.  The assignment is checked
     on a seeded sample of codes against all K centers; histogram, counts and vote are checked in
     full by giving the GPU's assignment to the oracle."""
     pq, oracle, W, torch, dev = env["pq"], env["oracle"], env["W"], env["torch"], env["dev"]
-    w = workload(cfg)
+    w = workload(cfg, **over)
     cw = W.codewords(w)
     tables_d = pq.build_tables(_dev(env, cw))
     _sync(env)
@@ -479,6 +480,14 @@ def test_config4_cnn_sampled(env):
 
 def test_config5_billion_sampled(env):
     _run_config_sampled(env, 5, 100_000, iters=1)
+
+
+@pytest.mark.skipif(os.environ.get("PQKM_SKIP_HUGE") == "1",
+                    reason="more than 2**32 codes: 60 GB of device memory, 35 GB of host memory, half a minute")
+def test_more_than_2_to_32_codes(env):
+    """Code indices beyond 32 bits: 65 scan launches, the atomic histogram path in chunks of 2**30 codes
+    (the sorted and owner paths index codes with 32 bits and are not taken)."""
+    _run_config_sampled(env, 5, 100_000, iters=1, N=(1 << 32) + 5000, K=64)
 
 
 # ------------------------------------------------------------------------------------ encode / decode (Sec. 2.2)
