@@ -119,3 +119,40 @@ def test_microbenchmark_library_loads_and_rejects_bad_arguments():
     mb.pqkm_microbench.restype = ctypes.c_int
     mb.pqkm_microbench.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
     assert mb.pqkm_microbench(0, None, None) == 1
+
+
+def test_header_is_plain_c_and_a_c_program_links(lib, tmp_path):
+    """include/pqkm.h compiles as strict C99 and as C++, and a C caller links against libpqkm.so (argument
+    checks only: nothing here touches a GPU)."""
+    import shutil
+    import subprocess
+
+    from paper_1709_03708_amd.binding import lib_path
+
+    gcc = shutil.which("gcc")
+    gxx = shutil.which("g++")
+    if gcc is None or gxx is None:
+        pytest.skip("no host C/C++ compiler")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "caller.c"
+    src.write_text(
+        '#include "pqkm.h"\n'
+        "#include <stdio.h>\n"
+        "int main(void) {\n"
+        "    /* invalid shapes and NULL pointers are rejected on the host, before any HIP call */\n"
+        "    if (pqkm_workspace_bytes(-1, 4, 10) != 0) return 1;\n"
+        "    if (pqkm_workspace_bytes(1000, 4, 10) == 0) return 2;\n"
+        "    if (pqkm_assign(NULL, -1, 4, NULL, 10, NULL, NULL, NULL, NULL, 0, NULL) != PQKM_ERR_SHAPE) return 3;\n"
+        "    if (pqkm_assign(NULL, 10, 4, NULL, 10, NULL, NULL, NULL, NULL, 0, NULL) != PQKM_ERR_NULL) return 4;\n"
+        '    printf("%s\\n", pqkm_status_string(PQKM_OK));\n'
+        "    return 0;\n"
+        "}\n")
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(lib_path())
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe),
+                    "-L", libdir, "-lpqkm", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
+    assert out.stdout.strip() == "ok"
+    cpp = tmp_path / "caller.cpp"
+    cpp.write_text('#include "pqkm.h"\nint main() { return pqkm_workspace_bytes(-1, 4, 10) == 0 ? 0 : 1; }\n')
+    subprocess.run([gxx, "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
