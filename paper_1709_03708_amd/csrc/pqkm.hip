@@ -36,7 +36,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, total;
+        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, pool_off, bseg_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -97,6 +97,15 @@ Carve carve(int64_t N, int M, int K)
         off += align256((size_t)na * sizeof(uint2));
         c.plan_off = off;
         off += align256(sizeof(GroupPlan));
+        // records the scan files by cluster group for the histogram (one scan launch, owner-path sizes only): every
+        // scan workgroup owns as many records as it has code positions (at most 4096); one segment per (group, workgroup)
+        c.pool_off = c.bseg_off = off;
+        if (hp.KT >= 1 && hp.groups <= 255 && N <= GROUP_CHUNK_MAX - 16384) {
+            c.pool_off = off;
+            off += align256((size_t)(na + 4096) * sizeof(uint2));
+            c.bseg_off = off;
+            off += align256((size_t)hp.groups * (size_t)(na / 2048 + 2) * sizeof(uint2));
+        }
     }
     // sorted-path histogram: code indices sorted by cluster (u32), cluster sizes, starts and cursors
     c.sidx_off = c.seg_off = off;
@@ -167,14 +176,14 @@ void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntile
                        ntiles, assign, dist);
 }
 
-template <int R, int THREADS, int DEPTH>
+template <int R, int THREADS, int DEPTH, bool BUCKET = false>
 void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, const float4* rows,
-                   int ntiles, int32_t* assign, float* dist, hipStream_t st)
+                   int ntiles, int32_t* assign, float* dist, hipStream_t st, BucketOut bo = BucketOut{})
 {
     constexpr int C = (THREADS / 4) * R;
     int64_t nwg = (N + C - 1) / C;
-    hipLaunchKernelGGL((assign_scan4p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N, gco,
-                       img, rows, ntiles, assign, dist);
+    hipLaunchKernelGGL((assign_scan4p_kernel<R, THREADS, DEPTH, BUCKET>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes,
+                       N, gco, img, rows, ntiles, assign, dist, bo);
 }
 
 template <int M, int R, int THREADS, int DEPTH = 1>
@@ -246,8 +255,11 @@ int scan4p_codes_per_slot(int64_t n_alloc)
     return best;
 }
 
+// bo != nullptr: the scan also files (code, center) records by cluster group for the histogram pass (variant 70
+// only); *nwg_out receives the number of scan workgroups = the row length of the segment table
 void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
-                         int ntiles, int32_t* assign, float* dist, hipStream_t st)
+                         int ntiles, int32_t* assign, float* dist, hipStream_t st, const BucketOut* bo = nullptr,
+                         int* nwg_out = nullptr)
 {
     int R = 0;
     switch (variant) {
@@ -259,6 +271,18 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
         case 75: R = 20; break;
         case 76: R = 16; break;
         default: R = 32; break;      // 77..79
+    }
+    if (bo) {
+        if (nwg_out) *nwg_out = (int)((n_alloc + 128 * R - 1) / (128 * R));
+        switch (R) {
+            case 16: launch_scan4p<16, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+            case 20: launch_scan4p<20, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+            case 24: launch_scan4p<24, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+            case 28: launch_scan4p<28, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+            case 31: launch_scan4p<31, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+            default: launch_scan4p<32, 512, 3, true>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, *bo); break;
+        }
+        return;
     }
     switch (R) {
         case 16: launch_scan4p<16, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
@@ -422,10 +446,17 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
 }
 inline bool variant_grouped(int M, int variant) { return (M == 4 || M == 8) && variant >= 70 && variant <= 79; }
 
+// The fused iteration's hand-over from the scan to the histogram: filled in by the caller (wanted, KT, ngroups),
+// completed by the assignment (produced, nwg) when the scan that ran could file its codes by cluster group.
+struct BucketLink {
+    bool wanted = false, produced = false;
+    int KT = 0, ngroups = 0, nwg = 0;
+};
+
 template <int M>
 pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers, int K, const float* tables,
                          int32_t* assign, float* dist, float* img, const Options& opt, const Carve& c, char* ws,
-                         bool reuse_groups, hipStream_t st)
+                         bool reuse_groups, hipStream_t st, BucketLink* link = nullptr)
 {
     constexpr int TK = 128 / M;
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
@@ -477,7 +508,14 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                  assign + n0, dist ? dist + n0 : nullptr, st);
-        else if (grouped)
+        else if (grouped && M == 4 && link && link->wanted && variant == 70 && N <= per_launch &&
+                 c.bseg_off != c.pool_off) {
+            BucketOut bo{reinterpret_cast<uint2*>(ws + c.pool_off), reinterpret_cast<uint2*>(ws + c.bseg_off), link->KT,
+                         link->ngroups};
+            launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows,
+                                (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st, &bo, &link->nwg);
+            link->produced = true;
+        } else if (grouped)
             launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows,
                                 (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st);
         else
@@ -490,7 +528,8 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
 }
 
 pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* centers, int K, const float* tables,
-                        int32_t* assign, float* dist, void* ws, hipStream_t st, bool reuse_groups = false)
+                        int32_t* assign, float* dist, void* ws, hipStream_t st, bool reuse_groups = false,
+                        BucketLink* link = nullptr)
 {
     if (N == 0) return PQKM_OK;
     Options opt;
@@ -509,7 +548,7 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
     float* img = reinterpret_cast<float*>(static_cast<char*>(ws) + c.img_off);
     char* wsc = static_cast<char*>(ws);
     switch (M) {
-        case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
+        case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st, link);
         case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
         case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
         default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
@@ -538,8 +577,34 @@ void sort_by_cluster(const int32_t* assign, int64_t N, int K, const Carve& c, ch
     *sidx_out = sidx;
 }
 
+// does the histogram take the LDS-privatised owner path for this problem (and the current options)?
+bool owner_histogram(const HistPlan& hp)
+{
+    int force;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        force = g_opt.hist_kernel;
+    }
+    return hp.KT >= 1 && hp.groups <= 255 && force != 1 && force != 3 && (force == 2 || hp.cheap);
+}
+
+// what a fused iteration asks of its assignment step: records by cluster group, when the histogram would
+// otherwise take the owner path (M = 4)
+BucketLink bucket_request(int64_t N, int M, int K)
+{
+    BucketLink l;
+    if (M != 4 || N < 1) return l;
+    const HistPlan hp = hist_plan(N, M, K);
+    if (!owner_histogram(hp)) return l;
+    l.wanted = true;
+    l.KT = hp.KT;
+    l.ngroups = (int)hp.groups;
+    return l;
+}
+
 pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* assign, int K, const float* tables,
-                        uint8_t* centers, uint32_t* hist, uint32_t* counts, void* ws, hipStream_t st)
+                        uint8_t* centers, uint32_t* hist, uint32_t* counts, void* ws, hipStream_t st,
+                        const BucketLink* link = nullptr)
 {
     Carve c = carve(N, M, K);
     if (!hist) hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.hist_off);
@@ -561,7 +626,22 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     int S = 1;
     size_t part_stride = 0;
     uint32_t* parts = hist;
-    if (owner) {
+    if (owner && link && link->produced && link->KT == hp.KT && link->ngroups == (int)hp.groups) {
+        // the scan of this iteration filed (code, center) records by cluster group: count from those
+        S = hp.S;
+        if (S > 1) {
+            parts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.parts_off);
+            part_stride = align256(c.hist_bytes) / sizeof(uint32_t);
+        }
+        const uint2* pool = reinterpret_cast<const uint2*>(static_cast<char*>(ws) + c.pool_off);
+        const uint2* bseg = reinterpret_cast<const uint2*>(static_cast<char*>(ws) + c.bseg_off);
+        if ((int64_t)hp.KT * M * L <= HIST_LDS_WORDS_SMALL)
+            hipLaunchKernelGGL((histogram_bucket_kernel<HIST_LDS_WORDS_SMALL>), dim3((unsigned)(hp.groups * S)),
+                               dim3(1024), 0, st, pool, bseg, link->nwg, K, hp.KT, S, parts, part_stride);
+        else
+            hipLaunchKernelGGL((histogram_bucket_kernel<HIST_LDS_WORDS>), dim3((unsigned)(hp.groups * S)), dim3(1024),
+                               0, st, pool, bseg, link->nwg, K, hp.KT, S, parts, part_stride);
+    } else if (owner) {
         S = hp.S;
         if (S > 1) {
             parts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.parts_off);
@@ -738,9 +818,10 @@ pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* ta
     if ((s = check_device()) != PQKM_OK) return s;
     for (int it = 0; it < iters; ++it) {
         // the codes do not change between iterations: regroup them for the scan once
-        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream, it > 0);
+        BucketLink link = bucket_request(N, M, K);
+        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream, it > 0, &link);
         if (s != PQKM_OK) return s;
-        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
+        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream, &link);
         if (s != PQKM_OK) return s;
     }
     return PQKM_OK;
@@ -795,10 +876,11 @@ pqkm_status pqkm_fit_until(const uint8_t* codes, int64_t N, int32_t M, const flo
         hipLaunchKernelGGL(fill_i32_kernel, dim3(fb), dim3(256), 0, st, prev, N, (int32_t)-1);
     }
     for (int it = 0; it < max_iters; ++it) {
-        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st, it > 0);
+        BucketLink link = bucket_request(N, M, K);
+        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st, it > 0, &link);
         if (s != PQKM_OK) return s;
         hipLaunchKernelGGL(iter_assign_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, assign, prev, dist, N, pa);
-        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, st);
+        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, st, &link);
         if (s != PQKM_OK) return s;
         hipLaunchKernelGGL(iter_hist_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, hist, (int64_t)K * M * L,
                            counts, K, ph);

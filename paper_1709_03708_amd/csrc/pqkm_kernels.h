@@ -888,13 +888,23 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
 // groups of four as possible have that property in all four subspaces (code_group_* kernels
 // below) as (code, original index) pairs; the result is written to the original index.
 // ---------------------------------------------------------------------------------------------
-template <int R, int THREADS, int DEPTH>
+// What the scan leaves for the histogram pass when BUCKET is set: workgroup w files its codes by cluster group
+// (KT consecutive clusters) into its own stretch [w*C, (w+1)*C) of `pool` as (code, center) records, the groups
+// one after the other, and notes (first record, number of records) of group g in seg[g * gridDim.x + w].
+struct BucketOut {
+    uint2* pool;
+    uint2* seg;
+    int KT;          // clusters per group
+    int ngroups;     // at most 256
+};
+
+template <int R, int THREADS, int DEPTH, bool BUCKET = false>
 __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* __restrict__ codes, int64_t N,
                                                                 const uint2* __restrict__ gco,
                                                                 const float4* __restrict__ img,
                                                                 const float4* __restrict__ rows, int ntiles,
                                                                 int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist)
+                                                                float* __restrict__ dist, BucketOut bo)
 {
     constexpr int LPS = 4, TK = 32;
     constexpr int SLOTS = THREADS / LPS;
@@ -904,6 +914,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
     constexpr uint32_t HPLANE = 16384;      // bytes per (m, h) plane: 256 subcodes x 16 centers
 
     __shared__ float4 tile[TILE_F4];
+    __shared__ uint32_t gcnt[BUCKET ? 256 : 1], gbase[BUCKET ? 256 : 1];   // codes per cluster group, first record
     const char* tb = reinterpret_cast<const char*>(tile);
 
     const int tid = threadIdx.x;
@@ -911,6 +922,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
     const int c = tid / LPS;
     const int64_t base = (int64_t)blockIdx.x * C;
     const uint32_t low15 = 0x7fffu;
+    if (BUCKET && tid < 256) gcnt[tid] = 0u;       // the tile loop's barriers come before its first use
 
     // per code two registers, each a 15-bit and a 17-bit field: the byte offset of the lane's piece in its row
     // (subspaces 0 and 1, low fields) and the same plus 64 KB (subspaces 2 and 3, high fields), so that every
@@ -1133,8 +1145,95 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
                 assign[dst] = (bi[e] == IDX_NONE) ? 0 : bi[e];
                 if (dist) dist[dst] = smin[e];
             }
+            if (BUCKET && i0 + e < CPL) {
+                // the code's 32-byte slot of records has been read (by this lane only): it now keeps the code, its
+                // center, its cluster group and its rank among the workgroup's codes of that group
+                const uint32_t k = (bi[e] == IDX_NONE) ? 0u : (uint32_t)bi[e];
+                uint32_t g = 0xffffffffu, rank = 0u;
+                if (og[e] != ORIGIN_NONE) {
+                    g = k / (uint32_t)bo.KT;
+                    g = g < 255u ? g : 255u;                     // k < K and at most 255 groups: never taken
+                    rank = atomicAdd(&gcnt[g], 1u);
+                }
+                const int j = (i0 + e) * THREADS + tid;
+                *reinterpret_cast<uint4*>(reinterpret_cast<char*>(tile) + (size_t)j * 32u) = make_uint4(pk[e], k, g, rank);
+            }
         }
     }
+    if (BUCKET) {
+        __syncthreads();
+        if (tid < 64) {                                          // exclusive prefix over the groups: lane l owns 4l .. 4l+3
+            const uint32_t a0 = gcnt[4 * tid], a1 = gcnt[4 * tid + 1], a2 = gcnt[4 * tid + 2], a3 = gcnt[4 * tid + 3];
+            const uint32_t mine = a0 + a1 + a2 + a3;
+            const uint32_t e0 = wave_inclusive_scan(mine) - mine, e1 = e0 + a0, e2 = e1 + a1, e3 = e2 + a2;
+            gbase[4 * tid] = e0;  gbase[4 * tid + 1] = e1;  gbase[4 * tid + 2] = e2;  gbase[4 * tid + 3] = e3;
+            const size_t nw = gridDim.x;
+            uint2* sg = bo.seg + blockIdx.x;
+            if (4 * tid < bo.ngroups) sg[(size_t)(4 * tid) * nw] = make_uint2((uint32_t)(base + e0), a0);
+            if (4 * tid + 1 < bo.ngroups) sg[(size_t)(4 * tid + 1) * nw] = make_uint2((uint32_t)(base + e1), a1);
+            if (4 * tid + 2 < bo.ngroups) sg[(size_t)(4 * tid + 2) * nw] = make_uint2((uint32_t)(base + e2), a2);
+            if (4 * tid + 3 < bo.ngroups) sg[(size_t)(4 * tid + 3) * nw] = make_uint2((uint32_t)(base + e3), a3);
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int i = 0; i < CPL; ++i) {
+            const int j = i * THREADS + tid;
+            const uint4 r = *reinterpret_cast<const uint4*>(tb + (size_t)j * 32u);
+            if (r.z != 0xffffffffu) bo.pool[base + gbase[r.z] + r.w] = make_uint2(r.x, r.y);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq. 7 from the records the scan filed by cluster group (M = 4): workgroup (g, s) owns group g
+// (KT clusters, private histograms in LDS as in the owner path) and the scan workgroups
+// w = s, s + S, ...; each of its waves takes some of them, reads group g's stretch of their
+// records (contiguous, (code, center) pairs) and counts with LDS atomics.  No pass over the
+// assignment array, no gather of codes: 8 bytes per code are read once.  Output as the owner
+// path's: the private histograms whole, S partial arrays when S > 1.
+// ---------------------------------------------------------------------------------------------
+template <int LDS_WORDS>
+__global__ __launch_bounds__(1024) void histogram_bucket_kernel(const uint2* __restrict__ pool,
+                                                                const uint2* __restrict__ seg, int nwg, int K,
+                                                                int KT, int S, uint32_t* __restrict__ hist,
+                                                                size_t part_stride)
+{
+    constexpr int M = 4;
+    __shared__ uint32_t lh[LDS_WORDS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x / S, s = blockIdx.x % S;
+    const int k0 = g * KT;
+    const int kt = (K - k0 < KT) ? K - k0 : KT;
+    const int words = kt * M * L;
+    for (int i = tid; i < words; i += 1024) lh[i] = 0u;
+    __syncthreads();
+    constexpr int SB = 4;                                   // segments whose records are in flight together
+    const int stride = 16 * S;
+    for (int w0 = s * 16 + wave; w0 < nwg; w0 += stride * SB) {
+        uint2 sg[SB];
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            const int w = w0 + u * stride;
+            sg[u] = w < nwg ? seg[(size_t)g * nwg + w] : make_uint2(0u, 0u);
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            for (uint32_t i = lane; i < sg[u].y; i += 64) {
+                const uint2 r = pool[(size_t)sg[u].x + i];
+                const uint32_t kk = r.y - (uint32_t)k0;
+                if (kk < (uint32_t)kt) {
+                    uint32_t* h = lh + (size_t)kk * M * L;
+                    atomicAdd(&h[0 * L + (r.x & 255u)], 1u);
+                    atomicAdd(&h[1 * L + ((r.x >> 8) & 255u)], 1u);
+                    atomicAdd(&h[2 * L + ((r.x >> 16) & 255u)], 1u);
+                    atomicAdd(&h[3 * L + (r.x >> 24)], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* out = hist + (size_t)s * part_stride + (size_t)k0 * M * L;
+    for (int i = tid; i < words; i += 1024) out[i] = lh[i];
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -375,6 +375,43 @@ def _run_config_full(env, cfg, iters, **over):
     return empties
 
 
+@pytest.mark.parametrize("N,K,kind", [(70_001, 130, "templates"), (300_007, 1000, "templates"), (131_072, 257, "skewed"),
+                                      (200_003, 600, "one_class"), (65_536, 4000, "templates")])
+def test_fit_files_codes_by_cluster_group(env, N, K, kind):
+    """pqkm_fit with 4-byte codes at owner-path sizes: the scan files (code, center) records by cluster group and
+    the histogram counts from those.  Centers, assignments, histograms and counts of the last iteration against
+    the oracle, for ragged N and K, cluster sizes from empty to huge, and codes of a single residue class."""
+    pq, oracle, W = env["pq"], env["oracle"], env["W"]
+    rng = np.random.default_rng(N + K)
+    w = workload(2, N=N, K=K)
+    tables = env["oracle"].build_tables(W.codewords(w))
+    if kind == "templates":
+        codes = W.codes_numpy(w)
+    elif kind == "skewed":
+        # nine tenths of the codes are copies of 3 codes: a few huge clusters, most groups nearly empty
+        codes = rng.integers(0, 256, size=(N, 4), dtype=np.uint8)
+        hot = rng.integers(0, 256, size=(3, 4), dtype=np.uint8)
+        pick = rng.random(N) < 0.9
+        codes[pick] = hot[rng.integers(0, 3, size=int(pick.sum()))]
+    else:
+        codes = (rng.integers(0, 64, size=(N, 4), dtype=np.uint8) * 4 + 1).astype(np.uint8)   # every subcode = 1 mod 4
+    codes = np.ascontiguousarray(codes)
+    cent0 = codes[rng.choice(N, size=K, replace=False)].copy()
+    d_codes, d_tables, d_cent = _dev(env, codes), _dev(env, tables), _dev(env, cent0)
+    torch = env["torch"]
+    hist = torch.empty((K, 4, 256), dtype=torch.int32, device=env["dev"])
+    counts = torch.empty((K,), dtype=torch.int32, device=env["dev"])
+    iters = 2
+    _, fa = pq.fit(d_codes, d_tables, d_cent, iters, hist=hist, counts=counts)
+    _sync(env)
+    rc, ra, rh, rcnt = oracle.fit(codes, tables, cent0, iters)
+    np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+    np.testing.assert_array_equal(u32(hist), rh)
+    np.testing.assert_array_equal(u32(counts), rcnt)
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+    progress(f"fused fit N={N} K={K} {kind}: bit-exact, {int((rcnt == 0).sum())} empty clusters")
+
+
 def test_config1_tiny_all_iterations(env):
     empties = _run_config_full(env, 1, workload(1).iters)
     assert empties > 0          # duplicate initial centers guarantee empty clusters here
