@@ -194,7 +194,8 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
  *                        conflict-free LDS reads when N >= 65536 and K >= 128, else the subspace-skewed
  *                        scan), 1..99 = one specific compiled scan and launch shape (for tuning sweeps;
  *                        e.g. 34 = the skewed M = 4 scan without regrouping, 70 = the regrouped one)
- *   "hist_kernel"        0 = choose automatically (default), 1 = force one global atomic
+ *   "hist_kernel"        0 = choose automatically (default; inside pqkm_fit / pqkm_fit_until with M = 4 this
+ *                        includes counting from records the scan files by cluster group), 1 = force one global atomic
  *                        per code and subspace, 2 = force the LDS-privatised histogram over cluster
  *                        groups (falls back when K needs more than 255 groups), 3 = force the
  *                        histogram over code indices sorted by cluster

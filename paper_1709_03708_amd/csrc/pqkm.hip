@@ -595,7 +595,12 @@ BucketLink bucket_request(int64_t N, int M, int K)
     BucketLink l;
     if (M != 4 || N < 1) return l;
     const HistPlan hp = hist_plan(N, M, K);
-    if (!owner_histogram(hp)) return l;
+    int force;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        force = g_opt.hist_kernel;
+    }
+    if (force != 0 || !owner_histogram(hp)) return l;     // a forced histogram kernel is used as named
     l.wanted = true;
     l.KT = hp.KT;
     l.ngroups = (int)hp.groups;
