@@ -376,7 +376,8 @@ def _run_config_full(env, cfg, iters, **over):
 
 
 @pytest.mark.parametrize("N,K,kind", [(70_001, 130, "templates"), (300_007, 1000, "templates"), (131_072, 257, "skewed"),
-                                      (200_003, 600, "one_class"), (65_536, 4000, "templates")])
+                                      (200_003, 600, "one_class"), (65_536, 4000, "templates"),
+                                      (150_001, 500, "several_launches"), (150_001, 500, "forced_owner")])
 def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     """pqkm_fit with 4-byte codes at owner-path sizes: the scan files (code, center) records by cluster group and
     the histogram counts from those.  Centers, assignments, histograms and counts of the last iteration against
@@ -385,7 +386,7 @@ def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     rng = np.random.default_rng(N + K)
     w = workload(2, N=N, K=K)
     tables = env["oracle"].build_tables(W.codewords(w))
-    if kind == "templates":
+    if kind in ("templates", "several_launches", "forced_owner"):
         codes = W.codes_numpy(w)
     elif kind == "skewed":
         # nine tenths of the codes are copies of 3 codes: a few huge clusters, most groups nearly empty
@@ -402,8 +403,18 @@ def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     hist = torch.empty((K, 4, 256), dtype=torch.int32, device=env["dev"])
     counts = torch.empty((K,), dtype=torch.int32, device=env["dev"])
     iters = 2
-    _, fa = pq.fit(d_codes, d_tables, d_cent, iters, hist=hist, counts=counts)
-    _sync(env)
+    # the hand-over needs one scan launch and the automatic histogram choice: with several launches, or a forced
+    # histogram kernel, the same call must fall back to the separate histogram pass
+    if kind == "several_launches":
+        pq.set_option("launch_codes_log2", 16)
+    if kind == "forced_owner":
+        pq.set_option("hist_kernel", 2)
+    try:
+        _, fa = pq.fit(d_codes, d_tables, d_cent, iters, hist=hist, counts=counts)
+        _sync(env)
+    finally:
+        pq.set_option("launch_codes_log2", 26)
+        pq.set_option("hist_kernel", 0)
     rc, ra, rh, rcnt = oracle.fit(codes, tables, cent0, iters)
     np.testing.assert_array_equal(fa.cpu().numpy(), ra)
     np.testing.assert_array_equal(u32(hist), rh)
