@@ -191,8 +191,9 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
  *                        scan that reads the tables through the cache hierarchy,
  *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
  *   "scan_variant"       0 = default scan of the LDS-tiled assignment (for M = 4: codes regrouped for
- *                        conflict-free LDS reads when N >= 65536 and K >= 128, else the subspace-skewed
- *                        scan), 1..99 = one specific compiled scan and launch shape (for tuning sweeps;
+ *                        conflict-free LDS reads when K >= 128 and N exceeds one round of 2048-code
+ *                        workgroups, else the subspace-skewed scan in a launch shape chosen by N),
+ *                        1..99 = one specific compiled scan and launch shape (for tuning sweeps;
  *                        e.g. 34 = the skewed M = 4 scan without regrouping, 70 = the regrouped one)
  *   "hist_kernel"        0 = choose automatically (default; inside pqkm_fit / pqkm_fit_until with M = 4 this
  *                        includes counting from records the scan files by cluster group), 1 = force one global atomic

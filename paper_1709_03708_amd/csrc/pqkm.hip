@@ -376,6 +376,8 @@ void launch_scan_M<4>(int variant, const uint8_t* codes, int64_t N, const float4
         case 34: launch_scan4s<16, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 36: launch_scan4s<16, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 37: launch_scan4s<8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 33: launch_scan4s<4, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 35: launch_scan4s<8, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 41: launch_scan4p<16, 1024, 1>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 44: launch_scan4p<24, 512, 4>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
         case 46: launch_scan4p<28, 512, 3>(codes, N, nullptr, img, rows, ntiles, assign, dist, st); break;
@@ -393,6 +395,8 @@ void launch_scan_M<8>(int variant, const uint8_t* codes, int64_t N, const float4
         case 3: launch_scan_skew<8, 12, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 4: launch_scan_skew<8, 16, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 5: launch_scan_skew<8, 24, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 6: launch_scan_skew<8, 2, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 7: launch_scan_skew<8, 4, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 40: launch_scan8p<24, 512, 4>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
         case 41: launch_scan8p<12, 1024, 2>(codes, N, nullptr, img, ntiles, assign, dist, st); break;
         default: launch_scan_skew<8, 8, 1024>(codes, N, img, ntiles, assign, dist, st); break;
@@ -407,6 +411,8 @@ void launch_scan_M<16>(int variant, const uint8_t* codes, int64_t N, const float
         case 2: launch_scan_skew<16, 3, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 3: launch_scan_skew<16, 6, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 4: launch_scan_skew<16, 10, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 6: launch_scan_skew<16, 2, 1024>(codes, N, img, ntiles, assign, dist, st); break;
+        case 7: launch_scan_skew<16, 1, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         default: launch_scan_skew<16, 4, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
@@ -420,6 +426,7 @@ void launch_scan_M<32>(int variant, const uint8_t* codes, int64_t N, const float
         case 3: launch_scan_skew<32, 4, 1024>(codes, N, img, ntiles, assign, dist, st); break;
         case 4: launch_scan_skew<32, 6, 512>(codes, N, img, ntiles, assign, dist, st); break;
         case 5: launch_scan_skew<32, 8, 512>(codes, N, img, ntiles, assign, dist, st); break;
+        case 6: launch_scan_skew<32, 1, 512>(codes, N, img, ntiles, assign, dist, st); break;
         default: launch_scan_skew<32, 2, 1024>(codes, N, img, ntiles, assign, dist, st); break;
     }
 }
@@ -437,12 +444,36 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
         if (special && !ok8) return 0;
         // 65536 residue classes: regrouping pays once most classes hold a few dozen codes
         if (variant == 0 && ok8 && K >= 256 && N >= ((int64_t)1 << 22)) return 70;
+        if (variant == 0) {
+            // skewed scan: while one round of workgroups covers the codes, the smallest shape that does so (measured
+            // per round at K = 1000: 139, 172, 220, 263 us for 512, 1024, 1536, 2048 codes per workgroup)
+            const int64_t ncu = cu_count();
+            return N <= ncu * 512 ? 6 : N <= ncu * 1024 ? 7 : N <= ncu * 1536 ? 2 : 0;
+        }
         return variant;
+    }
+    if ((M == 16 || M == 32) && variant == 0) {
+        // the same for the wider codes (M = 16: 270, 343, 440, 524 us; M = 32: 640, 690, -, 1066 us)
+        const int64_t ncu = cu_count();
+        if (M == 16) return N <= ncu * 512 ? 7 : N <= ncu * 1024 ? 6 : N <= ncu * 1536 ? 2 : 0;
+        return N <= ncu * 512 ? 6 : N <= ncu * 1024 ? 2 : 0;
     }
     if (M == 4 && !img32 && special) return 34;
     if (M != 4 || variant != 0) return variant;
-    if (K < 128 || N < 65536 || !img32) return 34;
-    return 70;                            // 32 codes per lane-slot, 512 threads: the fastest measured shape at every size
+    // The skewed scan needs no regrouping pass and comes in shapes of 512 to 4096 codes per workgroup; a workgroup's
+    // time grows with its codes (measured per round at K = 1000: 82, 107, 133, 254 us for 512, 1024, 2048, 4096),
+    // so while one round of workgroups covers all codes the smallest shape that does so wins, also over the
+    // regrouped scan (117 us and up per round plus the regrouping).  Beyond one round of 2048-code workgroups the
+    // regrouped scan is faster; with few centers (it needs K >= 128) the two largest skewed shapes remain.
+    const int64_t ncu = cu_count();
+    if (N <= ncu * 512) return 33;
+    if (N <= ncu * 1024) return 35;
+    if (N <= ncu * 2048) return 37;
+    if (K < 128 || !img32) {
+        const int64_t t34 = (((N + 4095) / 4096 + ncu - 1) / ncu) * 79, t37 = (((N + 2047) / 2048 + ncu - 1) / ncu) * 42;
+        return t37 < t34 ? 37 : 34;
+    }
+    return 70;                            // regrouped half-plane scan, codes per lane-slot chosen per launch
 }
 inline bool variant_grouped(int M, int variant) { return (M == 4 || M == 8) && variant >= 70 && variant <= 79; }
 

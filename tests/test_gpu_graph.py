@@ -13,7 +13,7 @@ from _util import progress, workload
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg,over,iters", [(1, {}, 3), (2, dict(N=150_000, K=600), 2), (3, dict(N=60_000, K=300), 2),
+@pytest.mark.parametrize("cfg,over,iters", [(1, {}, 3), (2, dict(N=150_000, K=600), 2), (2, dict(N=600_000, K=600), 2), (3, dict(N=60_000, K=300), 2),
                                              (3, dict(N=4_300_000, K=300), 2)])
 def test_fit_replays_in_a_graph(cfg, over, iters):
     import torch

@@ -89,7 +89,7 @@ def test_assign_generic_matches_oracle(env, M):
     _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=1)
 
 
-@pytest.mark.parametrize("variant", [1, 3, 5, 32, 34, 36, 37, 41, 44, 46, 48])
+@pytest.mark.parametrize("variant", [1, 3, 5, 32, 33, 34, 35, 36, 37, 41, 44, 46, 48])
 def test_assign_every_compiled_shape(env, variant):
     w = workload(1, N=9001, K=131, T=40)
     W = env["W"]
@@ -192,8 +192,9 @@ def test_regrouped_scan_in_several_launches(env):
     np.testing.assert_array_equal(gc.cpu().numpy().view(np.uint32), rcnt)
 
 
-@pytest.mark.parametrize("M,variant", [(8, 0), (8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (16, 0), (16, 1), (16, 2), (16, 3),
-                                       (16, 4), (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5)])
+@pytest.mark.parametrize("M,variant", [(8, 0), (8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (8, 6), (8, 7), (8, 10),
+                                       (16, 0), (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 7), (16, 10),
+                                       (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 10)])
 def test_assign_every_compiled_shape_wide_codes(env, M, variant):
     w = workload(1, M=M, D=16 * M, N=7001, K=77, T=40)
     W = env["W"]
@@ -375,12 +376,14 @@ def _run_config_full(env, cfg, iters, **over):
     return empties
 
 
-@pytest.mark.parametrize("N,K,kind", [(70_001, 130, "templates"), (300_007, 1000, "templates"), (131_072, 257, "skewed"),
-                                      (200_003, 600, "one_class"), (65_536, 4000, "templates"),
-                                      (150_001, 500, "several_launches"), (150_001, 500, "forced_owner")])
+@pytest.mark.parametrize("N,K,kind", [(530_001, 130, "templates"), (600_007, 1000, "templates"), (540_672, 257, "skewed"),
+                                      (550_003, 600, "one_class"), (525_000, 4000, "templates"),
+                                      (560_001, 500, "several_launches"), (560_001, 500, "forced_owner"),
+                                      (70_001, 130, "templates"), (300_007, 1000, "templates")])
 def test_fit_files_codes_by_cluster_group(env, N, K, kind):
-    """pqkm_fit with 4-byte codes at owner-path sizes: the scan files (code, center) records by cluster group and
-    the histogram counts from those.  Centers, assignments, histograms and counts of the last iteration against
+    """pqkm_fit with 4-byte codes at owner-path sizes: above one round of 2048-code workgroups (256 x 2048 codes) the
+    regrouped scan runs, files (code, center) records by cluster group and the histogram counts from those; the
+    two smaller cases take the skewed scan and the separate histogram pass through the same call.  Centers, assignments, histograms and counts of the last iteration against
     the oracle, for ragged N and K, cluster sizes from empty to huge, and codes of a single residue class."""
     pq, oracle, W = env["pq"], env["oracle"], env["W"]
     rng = np.random.default_rng(N + K)
