@@ -308,6 +308,47 @@ def test_random_shapes_assign_then_update(env, seed):
         np.testing.assert_array_equal(u32(hist), rh)
         np.testing.assert_array_equal(u32(counts), rcnt)
         np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+        # the same data through the fused iteration (two iterations; the oracle's whole loop)
+        d_cent = _dev(env, centers)
+        _, fa = pq.fit(_dev(env, codes), _dev(env, tables), d_cent, 2, hist=hist, counts=counts)
+        _sync(env)
+        rc, ra, rh, rcnt = oracle.fit(codes, tables, centers, 2)
+        np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_shapes_fused_iteration(env, seed):
+    """Seeded random shapes above one round of 2048-code workgroups (M = 4, K >= 128), where pqkm_fit runs the
+    regrouped scan with the scan -> histogram hand-over: three iterations against the oracle's loop."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(seed)
+    for case in range(4):
+        N = int(rng.integers(524_289, 900_000))
+        K = int(rng.integers(128, 1500))
+        kind = ("uniform", "skew", "few")[int(rng.integers(0, 3))]
+        if kind == "uniform":
+            codes = rng.integers(0, 256, (N, 4), dtype=np.uint8)
+        elif kind == "skew":
+            codes = (rng.integers(0, 256, (N, 4)) * rng.integers(0, 2, (N, 4)) | rng.integers(0, 4, (N, 1))).astype(np.uint8)
+        else:
+            codes = rng.integers(0, 5, (N, 4), dtype=np.uint8)
+        centers = codes[rng.integers(0, N, K)].copy()
+        tables = rand_tables(rng, 4, integer=bool(rng.integers(0, 2)))
+        progress(f"random fused case seed={seed} #{case}: N={N} K={K} {kind}")
+        torch = env["torch"]
+        hist = torch.empty((K, 4, 256), dtype=torch.int32, device=env["dev"])
+        counts = torch.empty((K,), dtype=torch.int32, device=env["dev"])
+        d_cent = _dev(env, centers)
+        _, fa = pq.fit(_dev(env, codes), _dev(env, tables), d_cent, 3, hist=hist, counts=counts)
+        _sync(env)
+        rc, ra, rh, rcnt = oracle.fit(codes, tables, centers, 3)
+        np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
 
 
 def test_update_empty_input_and_big_counts(env):
