@@ -662,7 +662,17 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     int S = 1;
     size_t part_stride = 0;
     uint32_t* parts = hist;
-    if (owner && link && link->produced && link->KT == hp.KT && link->ngroups == (int)hp.groups) {
+    const bool linked = owner && link && link->produced && link->KT == hp.KT && link->ngroups == (int)hp.groups;
+    if (linked && M == 4 && hp.KT <= VOTE_REC_KT && link->nwg <= VOTE_REC_SEGS) {
+        // the scan of this iteration filed (code, center) records by cluster group, and a vote workgroup can take
+        // one group (and one subspace): it counts its histograms itself -- no histogram pass at all
+        const uint2* pool = reinterpret_cast<const uint2*>(static_cast<char*>(ws) + c.pool_off);
+        const uint2* bseg = reinterpret_cast<const uint2*>(static_cast<char*>(ws) + c.bseg_off);
+        hipLaunchKernelGGL((vote_kernel<true>), dim3((unsigned)(hp.groups * M)), dim3(VOTE_THREADS), 0, st, hist, hist, 1,
+                           (size_t)0, counts, K, M, hp.KT, tables, centers, VoteRecords{pool, bseg, link->nwg});
+        return launched();
+    }
+    if (linked) {
         // the scan of this iteration filed (code, center) records by cluster group: count from those
         S = hp.S;
         if (S > 1) {
@@ -717,8 +727,8 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     if (cw > 16) cw = ((cw + vote_pass - 1) / vote_pass) * vote_pass;   // whole passes of the waves
     if (cw > VOTE_MAX_CW) cw = VOTE_MAX_CW;
     const int64_t blocks_per_m = ((int64_t)K + cw - 1) / cw;
-    hipLaunchKernelGGL(vote_kernel, dim3((unsigned)(blocks_per_m * M)), dim3(VOTE_THREADS), 0, st, hist, parts, S, part_stride,
-                       counts, K, M, (int)cw, tables, centers);
+    hipLaunchKernelGGL((vote_kernel<false>), dim3((unsigned)(blocks_per_m * M)), dim3(VOTE_THREADS), 0, st, hist, parts, S,
+                       part_stride, counts, K, M, (int)cw, tables, centers, VoteRecords{});
     return launched();
 }
 

@@ -2146,14 +2146,28 @@ constexpr int VOTE_THREADS = 1024;       // 16 waves: many row reads in flight
 constexpr int VOTE_WAVES = VOTE_THREADS / 64;
 constexpr int VOTE_CPW = 2;              // clusters per wave whose sums are held in registers together
 
+// REC: the histograms do not arrive from memory; the workgroup counts them itself, for its subspace, from the
+// (code, center) records that the M = 4 scan filed by cluster group (its CW clusters are one group: CW = KT <=
+// VOTE_REC_KT, the group's row of the segment table fits VOTE_REC_SEGS entries), and stores them to hist.
+constexpr int VOTE_REC_KT = 16;
+constexpr int VOTE_REC_SEGS = 1024;
+struct VoteRecords {
+    const uint2* pool;
+    const uint2* seg;
+    int nwg;
+};
+
+template <bool REC>
 __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict__ hist,
                                                             const uint32_t* __restrict__ parts, int S,
                                                             size_t part_stride, uint32_t* __restrict__ counts,
                                                             int K, int M, int CW, const float* __restrict__ tables,
-                                                            uint8_t* __restrict__ centers)
+                                                            uint8_t* __restrict__ centers, VoteRecords vr)
 {
     constexpr int NF = 8192 / VOTE_THREADS;     // float4 per thread per half of the table
     __shared__ float4 At[128 * 64];             // [row j of the half][lane: candidates 4 lane .. 4 lane + 3]
+    __shared__ uint32_t lhist[REC ? VOTE_REC_KT * L : 1];     // REC: bins of the workgroup's clusters, this subspace
+    __shared__ uint2 lseg[REC ? VOTE_REC_SEGS : 1];           // REC: the group's (first record, count) per scan workgroup
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int blocks_per_m = (K + CW - 1) / CW;
     const int m = blockIdx.x / blocks_per_m;
@@ -2165,6 +2179,12 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
     // bins chunk*64 + lane, chunk = 0..3, of one (cluster, subspace): the S <= 16 partial arrays are added, all
     // loads of a cluster in flight together (slices past S re-read the last one and are not added)
     auto load_bins = [&](size_t pair, uint32_t (&out)[4]) {
+        if (REC) {
+            const int cl = (int)(pair / (size_t)M) - c0;          // cluster inside the workgroup's group
+#pragma unroll
+            for (int chunk = 0; chunk < 4; ++chunk) out[chunk] = lhist[cl * L + chunk * 64 + lane];
+            return;
+        }
         const size_t at = pair * L + lane;
         if (S <= 1) {
 #pragma unroll
@@ -2201,11 +2221,46 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
             }
         }
     };
+    // REC: Eq. 7 for this workgroup's clusters and subspace: the group's row of the segment table goes to LDS, then
+    // a wave per stretch of records, sixteen stretches' loads in flight per wave, one LDS atomic per record.  This
+    // runs before the table rows are requested: vector-memory results return in order, and the record loads would
+    // otherwise wait behind 128 KB of table rows (measured: 3.5 us more per launch).
+    auto count_from_records = [&]() {
+        const int g = blockIdx.x % blocks_per_m;
+        for (int i = tid; i < VOTE_REC_KT * L; i += VOTE_THREADS) lhist[i] = 0u;
+        for (int i = tid; i < vr.nwg; i += VOTE_THREADS) lseg[i] = vr.seg[(size_t)g * vr.nwg + i];
+        __syncthreads();
+        const uint32_t sh = 8u * (uint32_t)m;
+        constexpr int SB = 16;
+        for (int w0 = wave; w0 < vr.nwg; w0 += SB * VOTE_WAVES) {
+            uint2 sg[SB], r[SB];
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const int w = w0 + u * VOTE_WAVES;
+                sg[u] = w < vr.nwg ? lseg[w] : make_uint2(0u, 0u);
+                r[u] = (uint32_t)lane < sg[u].y ? vr.pool[(size_t)sg[u].x + lane] : make_uint2(0u, 0xffffffffu);
+            }
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const uint32_t kk = r[u].y - (uint32_t)c0;
+                if (kk < (uint32_t)cn) atomicAdd(&lhist[kk * L + ((r[u].x >> sh) & 255u)], 1u);
+                // a stretch longer than a wave (a group holding most of a scan workgroup's codes)
+                for (uint32_t i = lane + 64; i < sg[u].y; i += 64) {
+                    const uint2 x = vr.pool[(size_t)sg[u].x + i];
+                    const uint32_t k2 = x.y - (uint32_t)c0;
+                    if (k2 < (uint32_t)cn) atomicAdd(&lhist[k2 * L + ((x.x >> sh) & 255u)], 1u);
+                }
+            }
+        }
+        __syncthreads();
+    };
+
     auto fma_row = [](float4& acc, float h, const float4 r) {
         acc.x = fmaf(h, r.x, acc.x); acc.y = fmaf(h, r.y, acc.y);
         acc.z = fmaf(h, r.z, acc.z); acc.w = fmaf(h, r.w, acc.w);
     };
 
+    if (REC) count_from_records();
     for (int b0 = 0; b0 < cn; b0 += VOTE_WAVES * VOTE_CPW) {
         v4f pf[NF];
 #pragma unroll
@@ -2275,7 +2330,7 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
             const int c = b0 + q * VOTE_WAVES + wave;
             if (c >= cn) continue;                                           // the same for the whole wave
             const size_t pair = (size_t)(c0 + c) * M + m;
-            if (S > 1) {
+            if (S > 1 || REC) {
 #pragma unroll
                 for (int chunk = 0; chunk < 4; ++chunk) hist[pair * L + chunk * 64 + lane] = hv[q][chunk];
             }
