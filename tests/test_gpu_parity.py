@@ -420,11 +420,14 @@ def _run_config_full(env, cfg, iters, **over):
 @pytest.mark.parametrize("N,K,kind", [(530_001, 130, "templates"), (600_007, 1000, "templates"), (540_672, 257, "skewed"),
                                       (550_003, 600, "one_class"), (525_000, 4000, "templates"),
                                       (560_001, 500, "several_launches"), (560_001, 500, "forced_owner"),
-                                      (70_001, 130, "templates"), (300_007, 1000, "templates")])
+                                      (70_001, 130, "templates"), (300_007, 1000, "templates"),
+                                      (4_500_000, 300, "templates")])
 def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     """pqkm_fit with 4-byte codes at owner-path sizes: above one round of 2048-code workgroups (256 x 2048 codes) the
-    regrouped scan runs, files (code, center) records by cluster group and the histogram counts from those; the
-    two smaller cases take the skewed scan and the separate histogram pass through the same call.  Centers, assignments, histograms and counts of the last iteration against
+    regrouped scan runs and files (code, center) records by cluster group; the vote counts from those itself when
+    a group has at most 16 clusters and there are at most 1024 scan workgroups, else the histogram kernel does
+    (K = 4000: 32 clusters per group; N = 4.5e6: more scan workgroups).  The two smaller cases take the skewed
+    scan and the separate histogram pass through the same call.  Centers, assignments, histograms and counts of the last iteration against
     the oracle, for ragged N and K, cluster sizes from empty to huge, and codes of a single residue class."""
     pq, oracle, W = env["pq"], env["oracle"], env["W"]
     rng = np.random.default_rng(N + K)
