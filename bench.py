@@ -2,19 +2,28 @@
 """Benchmark of the PQk-means iteration on one MI355X.
 
 A "step" is one whole iteration of Alg. 1 (assignment by linear scan, Eq. 5, then the
-sparse-voting update, Eq. 7-8) over the synthetic SIFT-like 32-bit workload (configuration 2:
-N = 1e6 codes, M = 4, K = 1e3 centers), issued through the C ABI.  The steps are issued the way
-the workload runs them: pqkm_fit calls of the configuration's iteration count (10 for
-configuration 2), each from the initial centers, so whatever pqkm_fit does once per call (it
-regroups the codes for the scan) is paid once per 10 iterations, inside the timed region.
-Inputs are generated on the GPU and are resident in HBM before the timed region.
+sparse-voting update, Eq. 7-8), issued through the C ABI.  The headline workload is the largest
+configuration, the billion-scale SIFT-like one (configuration 5: N = 1e9 four-byte codes,
+K = 1e5 centers, 4e14 table look-ups per step, about 15 s); `--config C` selects another.  The
+steps are issued the way the workload runs them: pqkm_fit calls of the configuration's
+iteration count (1 for configuration 5, 10 for configuration 2), each from the initial
+centers, so whatever pqkm_fit does once per call (it regroups the codes for the scan) is inside
+the timed region as often as in the workload.  Inputs are generated on the GPU and are
+resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` is code-center SDC evaluations per second over the whole step
 (N*K / time per iteration, update included); `assign_evals_per_s` counts the scan kernel alone.
 `roofline` is for the dominant kernel, the LDS-tiled assignment scan: achieved = N*K*M table
 lookups of 4 bytes per launch / the kernel's average duration (HIP events recorded by the
 library on the stream the kernel runs on), against the LDS gather peak of the chip
-(256 CUs x 2.4 GHz x 256 B/clk).  `cpu_baseline` is the CPU oracle timed on the host cores.
+(256 CUs x 2.4 GHz x 256 B/clk); `roofline.assign_step_frac` is the same work over the time of the
+whole assignment step (tile images and regrouping of the codes included).  `configs` holds the
+same figures for the other configurations (a few steps each).  `cpu_baseline` is the CPU
+oracle timed on the host cores, once on all of them and once on one thread.
+
+The default command must end within the caller's time limit whatever machine of the pool it
+lands on: after the first warm-up step of configuration 5 the total is projected, and if it
+would pass --time-budget seconds the headline falls back to configuration 4 (the line says so).
 
 Two things keep a sub-millisecond iteration honest: short-iteration workloads first run untimed
 for --prewarm-seconds (the GPU raises its clocks only after tens of milliseconds of load), and
@@ -168,13 +177,160 @@ def microbench(torch) -> int:
     return 0
 
 
+def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.0):
+    """Generate configuration `cfg`, run `warmup` untimed and `steps` timed iterations, and return the figures
+    (or None if the projected total would pass the time budget).  The scan kernel and the whole assignment
+    steps are timed by HIP event pairs the library records on the stream it launches on."""
+    w = W.CONFIGS[cfg]
+    N, M, K = w.N, w.M, w.K
+    tables = pq.build_tables(torch.from_numpy(W.codewords(w)).to(dev))
+    codes = W.codes_torch(w, dev)
+    init_idx = W.init_center_indices(w)
+    centers0 = torch.from_numpy(W.codes_at(w, init_idx)).to(dev)
+    centers = centers0.clone()
+    assign = torch.empty(N, dtype=torch.int32, device=dev)
+    ws = torch.empty(pq.workspace_bytes(N, M, K), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def run(n: int) -> int:
+        """`n` iterations as pqkm_fit calls of w.iters iterations, each from the initial centers."""
+        calls, left = 0, n
+        while left > 0:
+            it = min(left, w.iters)
+            centers.copy_(centers0)
+            pq.fit(codes, tables, centers, it, assign=assign, workspace=ws)
+            left -= it
+            calls += 1
+        return calls
+
+    short = float(N) * K * M <= 2e12
+    # The GPU raises its clocks only after some tens of milliseconds of load: a handful of sub-millisecond warm-up
+    # steps would leave the timed region on the ramp.  Workloads whose iteration is short are therefore run untimed
+    # for a fixed wall time first (the W warm-up steps then follow as asked).
+    prewarm_s = 0.0
+    if args.prewarm_seconds > 0 and short:
+        tp = time.perf_counter()
+        while time.perf_counter() - tp < args.prewarm_seconds:
+            run(w.iters)
+            torch.cuda.synchronize()
+        prewarm_s = time.perf_counter() - tp
+
+    # An event pair costs 3-4 us of stream time; next to a 0.25 ms iteration that is 3 % of `value`, so for
+    # short-iteration workloads the K steps are timed twice: once plain (`value`, `ms_per_step`) and once more with
+    # the event pairs (the roofline's kernel time; `ms_per_step_with_events`).  Long iterations are timed once, with
+    # the pairs.
+    ms_with_events = None
+    if short:
+        run(warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fit_calls = run(steps)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        pq.set_option("profile", 3)
+        run(warmup)
+        torch.cuda.synchronize()
+        pq.profile_read()                               # discard the warm-up launches
+        pq.profile_read_steps()
+        te0 = time.perf_counter()
+        run(steps)
+        torch.cuda.synchronize()
+        ms_with_events = (time.perf_counter() - te0) * 1e3 / steps
+    else:
+        pq.set_option("profile", 3)
+        if warmup > 0:
+            tw = time.perf_counter()
+            run(1)
+            torch.cuda.synchronize()
+            one = time.perf_counter() - tw
+            if budget > 0 and t_start is not None:
+                projected = (time.perf_counter() - t_start) + one * (warmup - 1 + steps) + args.reserve_seconds
+                if projected > budget:
+                    pq.set_option("profile", 0)
+                    pq.profile_read()
+                    pq.profile_read_steps()
+                    return {"skipped": True, "first_step_s": one, "projected_s": projected}
+            run(warmup - 1)
+            torch.cuda.synchronize()
+        pq.profile_read()                               # discard the warm-up launches
+        pq.profile_read_steps()
+        t0 = time.perf_counter()
+        fit_calls = run(steps)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    scan_ms_total, scan_launches = pq.profile_read()
+    step_ms_total, assign_steps = pq.profile_read_steps()
+    pq.set_option("profile", 0)
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    evals = float(N) * K
+    scan_ms = scan_ms_total / max(scan_launches, 1)
+    launches_per_step = scan_launches / steps
+    lookups_per_launch = evals * M / launches_per_step
+    achieved_gbs = lookups_per_launch * 4 / (scan_ms * 1e-3) / 1e9
+    assign_step_ms = step_ms_total / max(assign_steps, 1)
+    return {
+        "skipped": False, "w": w, "codes": codes, "tables": tables, "centers0": centers0,
+        "ms_per_step": ms_per_step, "value": evals / (ms_per_step * 1e-3), "fit_calls": fit_calls,
+        "prewarm_s": prewarm_s, "short": short, "ms_with_events": ms_with_events,
+        "scan_ms": scan_ms, "scan_ms_total": scan_ms_total, "scan_launches": scan_launches,
+        "achieved_gbs": achieved_gbs, "lookups_per_launch": lookups_per_launch,
+        "assign_step_ms": assign_step_ms,
+        "assign_step_frac": evals * M * 4 / (assign_step_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
+    }
+
+
+def workload_label(cfg, w) -> str:
+    return f"config {cfg} ({w.name}): N={w.N} uint8 codes, M={w.M}, K={w.K}, D={w.D}"
+
+
+def cpu_baseline(r, oracle) -> dict:
+    """The CPU oracle (assign + update) on a bounded sample of the headline workload: the first n codes against all
+    K centers, about 10 s on all host threads and about 10 s on one."""
+    w = r["w"]
+    K = w.K
+    h_tables = r["tables"].cpu().numpy()
+    cent = r["centers0"].cpu().numpy()
+    cores = oracle.max_threads()
+
+    def timed(threads: int, seconds: float):
+        oracle.set_threads(threads)
+        n_sub = int(min(w.N, max(2_000, seconds * 1e8 * threads / K)))
+        h_codes = r["codes"][:n_sub].cpu().numpy()
+        reps, c0 = 0, time.perf_counter()
+        while True:
+            a, _ = oracle.assign(h_codes, cent, h_tables, want_dist=False)
+            oracle.update(h_codes, a, h_tables, cent)
+            reps += 1
+            t_cpu = time.perf_counter() - c0
+            if t_cpu >= seconds or reps >= 200:
+                break
+        return float(n_sub) * K * reps / t_cpu, (f"{reps} oracle iterations (assign + update) over the first {n_sub} "
+                                                 f"codes x all {K} centers, {t_cpu:.1f} s")
+
+    v_all, s_all = timed(cores, 10.0)
+    v_one, s_one = timed(1, 8.0)
+    oracle.set_threads(cores)
+    return {"value": v_all, "unit": "SDC evaluations/s", "cores": cores, "kind": "oracle", "sample": s_all,
+            "single_thread": {"value": v_one, "cores": 1, "sample": s_one}}
+
+
 def main() -> int:
+    t_start = time.perf_counter()
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration (1-5); 2 is the benchmark's")
+    ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=5,
+                    help="headline workload configuration (1-5); 5, the largest, is the benchmark's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sub-configs", action="store_true",
+                    help="skip the few-step runs of the other configurations (the `configs` array)")
+    ap.add_argument("--time-budget", type=float, default=540.0,
+                    help="seconds the whole run may take; if configuration 5 would not fit (projected after its first "
+                         "warm-up step) the headline falls back to configuration 4; 0 = never fall back")
+    ap.add_argument("--reserve-seconds", type=float, default=70.0,
+                    help="part of the time budget kept for the other configurations and the CPU baseline")
     ap.add_argument("--prewarm-seconds", type=float, default=0.5,
                     help="untimed run before the warm-up steps so that the GPU clocks have ramped up (short iterations only)")
     ap.add_argument("--encoder", action="store_true",
@@ -215,148 +371,98 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "copies": 5}))
         return 0
-    w = W.CONFIGS[args.config]
-    N, M, K = w.N, w.M, w.K
     if args.encoder:
-        return encoder_bench(args, w, pq, torch, dev)
+        return encoder_bench(args, W.CONFIGS[args.config], pq, torch, dev)
     if args.naive_update:
-        return naive_update_bench(args, w, pq, torch, dev)
+        return naive_update_bench(args, W.CONFIGS[args.config], pq, torch, dev)
 
-    cw = W.codewords(w)
-    tables = pq.build_tables(torch.from_numpy(cw).to(dev))
-    codes = W.codes_torch(w, dev)
-    init_idx = W.init_center_indices(w)
-    centers0 = torch.from_numpy(W.codes_at(w, init_idx)).to(dev)
-    centers = centers0.clone()
-    assign = torch.empty(N, dtype=torch.int32, device=dev)
-    ws = torch.empty(pq.workspace_bytes(N, M, K), dtype=torch.uint8, device=dev)
-    torch.cuda.synchronize()
+    cfg = args.config
+    fallback = None
+    r = measure(args, cfg, args.steps, args.warmup, pq, W, torch, dev, t_start, args.time_budget if cfg == 5 else 0.0)
+    if r["skipped"]:
+        fallback = (f"configuration 5 would not fit the time budget of {args.time_budget:.0f} s on this machine (first "
+                    f"step {r['first_step_s']:.1f} s, projected {r['projected_s']:.0f} s for {args.warmup} + {args.steps} "
+                    f"steps); the headline is configuration 4, the largest that fits")
+        print("bench.py: " + fallback, file=sys.stderr)
+        r = None
+        torch.cuda.empty_cache()
+        cfg = 4
+        r = measure(args, cfg, args.steps, args.warmup, pq, W, torch, dev)
+    w = r["w"]
+    N, M, K = w.N, w.M, w.K
 
-    def run(steps: int) -> int:
-        """`steps` iterations as pqkm_fit calls of w.iters iterations, each from the initial centers."""
-        calls, left = 0, steps
-        while left > 0:
-            it = min(left, w.iters)
-            centers.copy_(centers0)
-            pq.fit(codes, tables, centers, it, assign=assign, workspace=ws)
-            left -= it
-            calls += 1
-        return calls
-
-    # The GPU raises its clocks only after some tens of milliseconds of load: a handful of sub-millisecond warm-up
-    # steps would leave the timed region on the ramp.  Workloads whose iteration is short are therefore run untimed
-    # for a fixed wall time first (the W warm-up steps then follow as asked).
-    prewarm_s = 0.0
-    if args.prewarm_seconds > 0 and float(N) * K * M <= 2e12:
-        tp = time.perf_counter()
-        while time.perf_counter() - tp < args.prewarm_seconds:
-            run(w.iters)
-            torch.cuda.synchronize()
-        prewarm_s = time.perf_counter() - tp
-
-    # The scan kernel's duration comes from HIP event pairs that the library records around every scan launch on
-    # the stream it launches on.  A pair costs 3-4 us of stream time; next to a 0.25 ms iteration that is 3 % of
-    # `value`, so for short-iteration workloads the K steps are timed twice: once plain (`value`, `ms_per_step`)
-    # and once more with the event pairs (the roofline's kernel time; `ms_per_step_with_events`).  Long iterations
-    # are timed once, with the pairs.
-    two_pass = float(N) * K * M <= 2e12
-    ms_with_events = None
-    if two_pass:
-        run(args.warmup)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        fit_calls = run(args.steps)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        pq.set_option("profile", 1)
-        run(args.warmup)
-        torch.cuda.synchronize()
-        pq.profile_read()                               # discard the warm-up launches
-        te0 = time.perf_counter()
-        run(args.steps)
-        torch.cuda.synchronize()
-        ms_with_events = (time.perf_counter() - te0) * 1e3 / args.steps
-    else:
-        pq.set_option("profile", 1)
-        run(args.warmup)
-        torch.cuda.synchronize()
-        pq.profile_read()                               # discard the warm-up launches
-        t0 = time.perf_counter()
-        fit_calls = run(args.steps)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    scan_ms_total, scan_launches = pq.profile_read()
-    pq.set_option("profile", 0)
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    evals = float(N) * K
-    value = evals / (ms_per_step * 1e-3)
-    scan_ms = scan_ms_total / max(scan_launches, 1)
-    launches_per_step = scan_launches / args.steps
-    lookups_per_launch = evals * M / launches_per_step
-    achieved_gbs = lookups_per_launch * 4 / (scan_ms * 1e-3) / 1e9
-
-    # HBM traffic of the scan kernel, from the committed rocprofv3 --pmc summary if it covers this workload
-    traffic = None
+    # HBM traffic of the scan kernel: from the committed rocprofv3 --pmc summary of this workload (FETCH_SIZE and
+    # WRITE_SIZE scaled by a copy of known size), not a value of this run
+    traffic, traffic_src = None, None
     tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
     if os.path.exists(tfile):
         try:
             traffic = json.load(open(tfile)).get("scan_bytes_per_launch")
+            traffic_src = f"committed profile profiles/traffic_{w.name}.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)"
         except Exception:
             traffic = None
 
     out = {
         "metric": "code-center SDC evaluations/sec in assignment (N*K/s); seconds per PQk-means iter",
-        "value": value,
+        "value": r["value"],
         "unit": "SDC evaluations/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "sec_per_iter": ms_per_step * 1e-3,
-        "assign_evals_per_s": evals * args.steps / (scan_ms_total * 1e-3),
+        "ms_per_step": r["ms_per_step"],
+        "sec_per_iter": r["ms_per_step"] * 1e-3,
+        "assign_evals_per_s": float(N) * K * args.steps / (r["scan_ms_total"] * 1e-3),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"config {args.config} ({w.name}): N={N} uint8 codes, M={M}, K={K}, D={w.D}",
-                   "N": N, "M": M, "K": K, "iterations_timed": args.steps, "fit_calls": fit_calls,
-                   "iterations_per_fit_call": w.iters, "prewarm_s": round(prewarm_s, 3)},
+        "config": {"workload": workload_label(cfg, w),
+                   "N": N, "M": M, "K": K, "iterations_timed": args.steps, "fit_calls": r["fit_calls"],
+                   "iterations_per_fit_call": w.iters, "prewarm_s": round(r["prewarm_s"], 3)},
         "roofline": {"bound": "lds", "kernel": "assign_scan (LDS-tiled linear scan, Eq. 5)",
-                     "achieved": achieved_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved_gbs / LDS_PEAK_GBS, "traffic": traffic,
-                     "avg_kernel_ms": scan_ms, "launches": scan_launches,
+                     "achieved": r["achieved_gbs"], "peak": LDS_PEAK_GBS, "unit": "GB/s",
+                     "frac": r["achieved_gbs"] / LDS_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_src,
+                     "avg_kernel_ms": r["scan_ms"], "launches": r["scan_launches"],
                      "timed_in": ("a second pass of the same steps with HIP event pairs around every scan launch"
-                                  if two_pass else "the timed region (HIP event pairs around every scan launch)"),
-                     "ms_per_step_with_events": ms_with_events if two_pass else ms_per_step,
-                     "lookups_per_s": lookups_per_launch / (scan_ms * 1e-3),
-                     "hbm_algorithmic_gbs": (N * M + 4 * N) / (scan_ms * 1e-3) / 1e9,
+                                  if r["short"] else "the timed region (HIP event pairs around every scan launch)"),
+                     "ms_per_step_with_events": r["ms_with_events"] if r["short"] else r["ms_per_step"],
+                     "assign_step_ms": r["assign_step_ms"], "assign_step_frac": r["assign_step_frac"],
+                     "lookups_per_s": r["lookups_per_launch"] / (r["scan_ms"] * 1e-3),
+                     "hbm_algorithmic_gbs": (N * M + 4 * N) / (r["scan_ms_total"] / args.steps * 1e-3) / 1e9,
                      "hbm_peak_gbs": HBM_PEAK_GBS},
     }
+    if fallback:
+        out["config"]["fallback"] = fallback
 
+    cpu = None
     if not args.no_cpu_baseline:
         import oracle
 
-        h_codes = codes.cpu().numpy()
-        h_tables = tables.cpu().numpy()
-        cent = centers0.cpu().numpy()
-        cores = oracle.max_threads()
-        # bounded sample: first n_sub codes, sized for about 10 s of CPU work at ~1e8 evaluations/s/thread
-        n_sub = int(min(N, max(10_000, 10.0 * 1e8 * cores / K)))
-        reps, t_cpu = 0, 0.0
-        c0 = time.perf_counter()
-        while True:
-            a, _ = oracle.assign(h_codes[:n_sub], cent, h_tables, want_dist=False)
-            cent2, _, _ = oracle.update(h_codes[:n_sub], a, h_tables, cent)
-            reps += 1
-            t_cpu = time.perf_counter() - c0
-            if t_cpu >= 10.0 or reps >= 200:
-                break
-        out["cpu_baseline"] = {"value": float(n_sub) * K * reps / t_cpu, "unit": "SDC evaluations/s",
-                               "cores": cores, "kind": "oracle",
-                               "sample": f"{reps} oracle iterations (assign + update) over the first {n_sub} codes "
-                                         f"x all {K} centers, {t_cpu:.1f} s"}
+        cpu = cpu_baseline(r, oracle)
+    r = None
+    torch.cuda.empty_cache()
+
+    if not args.no_sub_configs:
+        subs = []
+        for c in (2, 3, 4):
+            if c == cfg:
+                continue
+            if args.time_budget > 0 and time.perf_counter() - t_start > args.time_budget - 20:
+                subs.append({"config": c, "skipped": "time budget"})
+                continue
+            sr = measure(args, c, 3, 1, pq, W, torch, dev)
+            sw = sr["w"]
+            subs.append({"config": c, "workload": workload_label(c, sw), "steps": 3, "warmup": 1,
+                         "ms_per_step": sr["ms_per_step"], "value": sr["value"],
+                         "avg_kernel_ms": sr["scan_ms"], "launches": sr["scan_launches"],
+                         "frac": sr["achieved_gbs"] / LDS_PEAK_GBS, "assign_step_ms": sr["assign_step_ms"],
+                         "assign_step_frac": sr["assign_step_frac"]})
+            sr = None
+            torch.cuda.empty_cache()
+        out["configs"] = subs
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
     return 0
 

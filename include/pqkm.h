@@ -20,7 +20,7 @@
  *     enqueued work is kernels only -- no memset or copy nodes -- so a caller
  *     may capture pqkm_build_tables, pqkm_encode, pqkm_decode, pqkm_assign,
  *     pqkm_update, pqkm_update_naive and pqkm_fit in a HIP graph (with the
- *     "profile" option off) and replay it; the workspace need not keep its
+ *     "profile" option of pqkm_tuning.h off) and replay it; the workspace need not keep its
  *     contents between replays.
  *   - `workspace` is device scratch of at least
  *     pqkm_workspace_bytes(N, M, K) bytes, 256-byte aligned, used only during
@@ -181,41 +181,6 @@ pqkm_status pqkm_fit_until(const uint8_t *codes, int64_t N, int32_t M, const flo
                            uint8_t *centers, int32_t max_iters, int32_t *assign, uint32_t *hist,
                            uint32_t *counts, pqkm_iter_stats *stats, int32_t *iters_done,
                            void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Tuning and measurement hooks (not part of the method).
- *
- * pqkm_set_option: process-wide integer knobs, by name (host string).  Unknown
- * name or out-of-range value -> PQKM_ERR_SHAPE.  Names:
- *   "assign_kernel"      0 = choose automatically (default), 1 = force the generic
- *                        scan that reads the tables through the cache hierarchy,
- *                        2 = force the LDS-tiled scan (M in {4, 8, 16, 32} only)
- *   "scan_variant"       0 = default scan of the LDS-tiled assignment (for M = 4: codes regrouped for
- *                        conflict-free LDS reads when K >= 128 and N exceeds one round of 2048-code
- *                        workgroups, else the subspace-skewed scan in a launch shape chosen by N),
- *                        1..99 = one specific compiled scan and launch shape (for tuning sweeps;
- *                        e.g. 34 = the skewed M = 4 scan without regrouping, 70 = the regrouped one)
- *   "hist_kernel"        0 = choose automatically (default; inside pqkm_fit / pqkm_fit_until with M = 4 this
- *                        includes counting from records the scan files by cluster group), 1 = force one global atomic
- *                        per code and subspace, 2 = force the LDS-privatised histogram over cluster
- *                        groups (falls back when K needs more than 255 groups), 3 = force the
- *                        histogram over code indices sorted by cluster
- *   "hist_groups"        target number of cluster groups of the LDS-privatised histogram,
- *                        1..255 (default 64); changes pqkm_workspace_bytes, so set it before
- *                        sizing the workspace
- *   "launch_codes_log2"  the scan is issued in launches of 2^value codes (default 26)
- *   "profile"            1 = bracket every scan-kernel launch with a pair of HIP
- *                        events on the caller's stream (events are created on
- *                        first use and reused; this is the one place the library
- *                        creates HIP objects), 0 = off (default)
- *
- * pqkm_profile_read: waits for the recorded stop events, returns the summed
- * elapsed time of the bracketed scan launches in milliseconds and their number,
- * and resets the record.  The only entry point that blocks the host.
- *   total_ms, launches   host pointers, out
- */
-pqkm_status pqkm_set_option(const char *name, int32_t value);
-pqkm_status pqkm_profile_read(double *total_ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

@@ -44,8 +44,9 @@ def load():
         lib.pqkm_decode.argtypes = [vp, i64, i32, i32, vp, vp, vp]
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        lib.pqkm_profile_read_steps.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
-                  "pqkm_profile_read", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"):
+                  "pqkm_profile_read", "pqkm_profile_read_steps", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -262,4 +263,11 @@ def profile_read():
     """-> (total milliseconds of the bracketed scan launches, number of launches)."""
     ms, n = ctypes.c_double(0), ctypes.c_int64(0)
     _check(load().pqkm_profile_read(ctypes.byref(ms), ctypes.byref(n)), "pqkm_profile_read")
+    return ms.value, n.value
+
+
+def profile_read_steps():
+    """-> (total milliseconds of the bracketed whole assignment steps, their number)."""
+    ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+    _check(load().pqkm_profile_read_steps(ctypes.byref(ms), ctypes.byref(n)), "pqkm_profile_read_steps")
     return ms.value, n.value

@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libpqkm.so")
 SOURCES = [os.path.join(HERE, "csrc", "pqkm.hip")]
-DEPS = SOURCES + [os.path.join(HERE, "csrc", "pqkm_kernels.h"), os.path.join(ROOT, "include", "pqkm.h")]
+DEPS = SOURCES + [os.path.join(HERE, "csrc", "pqkm_kernels.h"), os.path.join(ROOT, "include", "pqkm.h"),
+                  os.path.join(ROOT, "include", "pqkm_tuning.h")]
 MICROBENCH_LIB = os.path.join(HERE, "libpqkm_microbench.so")          # measurement code, loaded by bench.py only
 MICROBENCH_SOURCES = [os.path.join(HERE, "csrc", "microbench.hip")]
 

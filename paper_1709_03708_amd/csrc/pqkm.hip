@@ -1,6 +1,7 @@
 // C ABI of the PQk-means iteration for gfx950: argument validation, workspace carving and
 // kernel launches.  Every entry point is declared and documented in include/pqkm.h.
 #include "pqkm.h"
+#include "pqkm_tuning.h"
 
 #include <hip/hip_runtime.h>
 #include <string.h>
@@ -20,16 +21,60 @@ struct Options {
     int assign_kernel = 0;   // 0 auto, 1 generic, 2 tiled
     int scan_variant = 0;    // 0 auto, else a specific instantiation (tuning)
     int hist_kernel = 0;     // 0 auto, 1 global atomics, 2 LDS-privatised owner path, 3 sorted by cluster
-    int profile = 0;         // bracket scan kernels with events
+    int profile = 0;         // bit 0: bracket scan kernels with events, bit 1: bracket whole assignment steps
     int64_t launch_codes = (int64_t)1 << 26;   // codes per scan launch
 };
 Options g_opt;
 std::mutex g_mu;
-std::atomic<int> g_hist_groups{64};    // target number of cluster groups of the LDS-privatised histogram (measured best)
+constexpr int HIST_GROUPS = 64;        // target number of cluster groups of the LDS-privatised histogram (measured best)
+
+// Every entry point reads the process-wide options once, here, and passes the copy down: a call never sees a
+// change that another thread makes while it runs.
+Options options_snapshot()
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    return g_opt;
+}
 
 struct EventPair { hipEvent_t a, b; };
-std::vector<EventPair> g_pool;      // all events ever created
-size_t g_used = 0;                  // pairs recorded since the last read
+struct EventLog {
+    std::vector<EventPair> pool;    // all events ever created
+    size_t used = 0;                // pairs recorded since the last read
+};
+EventLog g_scan_log, g_step_log;    // around every scan launch / around every whole assignment step
+
+// start of a bracket: takes (or creates) a pair and records its first event; false if none could be had
+bool log_begin(EventLog& log, hipStream_t st, EventPair* ev)
+{
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (log.used == log.pool.size()) {
+            EventPair e{};
+            if (hipEventCreate(&e.a) == hipSuccess && hipEventCreate(&e.b) == hipSuccess) log.pool.push_back(e);
+        }
+        if (log.used == log.pool.size()) return false;
+        *ev = log.pool[log.used++];
+    }
+    hipEventRecord(ev->a, st);
+    return true;
+}
+
+pqkm_status log_read(EventLog& log, double* total_ms, int64_t* count)
+{
+    if (!total_ms || !count) return PQKM_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    double tot = 0.0;
+    for (size_t i = 0; i < log.used; ++i) {
+        if (hipEventSynchronize(log.pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, log.pool[i].a, log.pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
+        tot += ms;
+    }
+    *total_ms = tot;
+    *count = (int64_t)log.used;
+    log.used = 0;
+    return PQKM_OK;
+}
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
@@ -51,8 +96,8 @@ HistPlan hist_plan(int64_t N, int M, int K)
     HistPlan p{};
     const int kt_max = (HIST_LDS_WORDS / L) / M;           // 128 KB of LDS / (M KB per cluster)
     if (kt_max < 1) return p;
-    // about g_hist_groups groups (a byte names at most 255), within the LDS budget
-    const int hg = g_hist_groups.load();
+    // about HIST_GROUPS groups (a byte names at most 255), within the LDS budget
+    const int hg = HIST_GROUPS;
     int kt = (K + hg - 1) / hg;
     if (kt > kt_max) kt = kt_max;
     p.KT = kt;
@@ -523,19 +568,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             if (rs != PQKM_OK) return PQKM_ERR_DEVICE;
         }
         EventPair ev{};
-        bool prof = false;
-        if (opt.profile) {
-            std::lock_guard<std::mutex> lk(g_mu);
-            if (g_used == g_pool.size()) {
-                EventPair e{};
-                if (hipEventCreate(&e.a) == hipSuccess && hipEventCreate(&e.b) == hipSuccess) g_pool.push_back(e);
-            }
-            if (g_used < g_pool.size()) {
-                ev = g_pool[g_used++];
-                prof = true;
-            }
-        }
-        if (prof) hipEventRecord(ev.a, st);
+        const bool prof = (opt.profile & 1) && log_begin(g_scan_log, st, &ev);
         if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                  assign + n0, dist ? dist + n0 : nullptr, st);
@@ -558,16 +591,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     return PQKM_OK;
 }
 
-pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* centers, int K, const float* tables,
-                        int32_t* assign, float* dist, void* ws, hipStream_t st, bool reuse_groups = false,
-                        BucketLink* link = nullptr)
+pqkm_status assign_core(const Options& opt, const Carve& c, const uint8_t* codes, int64_t N, int M,
+                        const uint8_t* centers, int K, const float* tables, int32_t* assign, float* dist, void* ws,
+                        hipStream_t st, bool reuse_groups, BucketLink* link)
 {
-    if (N == 0) return PQKM_OK;
-    Options opt;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        opt = g_opt;
-    }
     bool tiled = tiled_M(M) && opt.assign_kernel != 1 && ((uintptr_t)codes & 3) == 0;
     if (opt.assign_kernel == 2 && !tiled) return PQKM_ERR_SHAPE;
     if (!tiled) {
@@ -575,7 +602,6 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
                            centers, K, tables, assign, dist);
         return launched();
     }
-    Carve c = carve(N, M, K);
     float* img = reinterpret_cast<float*>(static_cast<char*>(ws) + c.img_off);
     char* wsc = static_cast<char*>(ws);
     switch (M) {
@@ -584,6 +610,19 @@ pqkm_status assign_impl(const uint8_t* codes, int64_t N, int M, const uint8_t* c
         case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
         default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
     }
+}
+
+// one whole assignment step (tile images, regrouping where it is due, scan launches), optionally bracketed by events
+pqkm_status assign_impl(const Options& opt, const Carve& c, const uint8_t* codes, int64_t N, int M,
+                        const uint8_t* centers, int K, const float* tables, int32_t* assign, float* dist, void* ws,
+                        hipStream_t st, bool reuse_groups = false, BucketLink* link = nullptr)
+{
+    if (N == 0) return PQKM_OK;
+    EventPair ev{};
+    const bool prof = (opt.profile & 2) && log_begin(g_step_log, st, &ev);
+    const pqkm_status s = assign_core(opt, c, codes, N, M, centers, K, tables, assign, dist, ws, st, reuse_groups, link);
+    if (prof) hipEventRecord(ev.b, st);
+    return s;
 }
 
 // counting sort of the code indices by cluster into the workspace: start[0..K] and sidx[0..#valid)
@@ -608,41 +647,31 @@ void sort_by_cluster(const int32_t* assign, int64_t N, int K, const Carve& c, ch
     *sidx_out = sidx;
 }
 
-// does the histogram take the LDS-privatised owner path for this problem (and the current options)?
-bool owner_histogram(const HistPlan& hp)
+// does the histogram take the LDS-privatised owner path for this problem (and the call's options)?
+bool owner_histogram(const HistPlan& hp, int force)
 {
-    int force;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        force = g_opt.hist_kernel;
-    }
     return hp.KT >= 1 && hp.groups <= 255 && force != 1 && force != 3 && (force == 2 || hp.cheap);
 }
 
 // what a fused iteration asks of its assignment step: records by cluster group, when the histogram would
 // otherwise take the owner path (M = 4)
-BucketLink bucket_request(int64_t N, int M, int K)
+BucketLink bucket_request(const Options& opt, int64_t N, int M, int K)
 {
     BucketLink l;
     if (M != 4 || N < 1) return l;
     const HistPlan hp = hist_plan(N, M, K);
-    int force;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        force = g_opt.hist_kernel;
-    }
-    if (force != 0 || !owner_histogram(hp)) return l;     // a forced histogram kernel is used as named
+    const int force = opt.hist_kernel;
+    if (force != 0 || !owner_histogram(hp, force)) return l;     // a forced histogram kernel is used as named
     l.wanted = true;
     l.KT = hp.KT;
     l.ngroups = (int)hp.groups;
     return l;
 }
 
-pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* assign, int K, const float* tables,
-                        uint8_t* centers, uint32_t* hist, uint32_t* counts, void* ws, hipStream_t st,
-                        const BucketLink* link = nullptr)
+pqkm_status update_impl(const Options& opt, const Carve& c, const uint8_t* codes, int64_t N, int M,
+                        const int32_t* assign, int K, const float* tables, uint8_t* centers, uint32_t* hist,
+                        uint32_t* counts, void* ws, hipStream_t st, const BucketLink* link = nullptr)
 {
-    Carve c = carve(N, M, K);
     if (!hist) hist = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.hist_off);
     if (!counts) counts = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + c.counts_off);
     const int64_t nh = (int64_t)K * M * L;
@@ -653,12 +682,8 @@ pqkm_status update_impl(const uint8_t* codes, int64_t N, int M, const int32_t* a
     // Owner path (LDS-privatised, no global atomics) while streaming the assignment array once per cluster
     // group is cheap; otherwise one global atomic per code and subspace into a zeroed histogram.
     const HistPlan hp = hist_plan(N, M, K);
-    int force;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        force = g_opt.hist_kernel;
-    }
-    const bool owner = hp.KT >= 1 && hp.groups <= 255 && force != 1 && force != 3 && (force == 2 || hp.cheap);
+    const int force = opt.hist_kernel;
+    const bool owner = owner_histogram(hp, force);
     int S = 1;
     size_t part_stride = 0;
     uint32_t* parts = hist;
@@ -816,10 +841,12 @@ pqkm_status pqkm_assign(const uint8_t* codes, int64_t N, int32_t M, const uint8_
 {
     if (!shape_ok(N, M, K)) return PQKM_ERR_SHAPE;
     if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
-    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    const Carve c = carve(N, M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, c.total);
     if (s != PQKM_OK) return s;
     if ((s = check_device()) != PQKM_OK) return s;
-    return assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, (hipStream_t)stream);
+    return assign_impl(options_snapshot(), c, codes, N, M, centers, K, tables, assign, dist, workspace,
+                       (hipStream_t)stream);
 }
 
 pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,
@@ -828,10 +855,12 @@ pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_
 {
     if (!shape_ok(N, M, K)) return PQKM_ERR_SHAPE;
     if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
-    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    const Carve c = carve(N, M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, c.total);
     if (s != PQKM_OK) return s;
     if ((s = check_device()) != PQKM_OK) return s;
-    return update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream);
+    return update_impl(options_snapshot(), c, codes, N, M, assign, K, tables, centers, hist, counts, workspace,
+                       (hipStream_t)stream);
 }
 
 pqkm_status pqkm_update_naive(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,
@@ -859,15 +888,19 @@ pqkm_status pqkm_fit(const uint8_t* codes, int64_t N, int32_t M, const float* ta
 {
     if (!shape_ok(N, M, K) || iters < 0) return PQKM_ERR_SHAPE;
     if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
-    pqkm_status s = check_workspace(workspace, workspace_bytes, carve(N, M, K).total);
+    const Carve c = carve(N, M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, c.total);
     if (s != PQKM_OK) return s;
     if ((s = check_device()) != PQKM_OK) return s;
+    const Options opt = options_snapshot();
     for (int it = 0; it < iters; ++it) {
         // the codes do not change between iterations: regroup them for the scan once
-        BucketLink link = bucket_request(N, M, K);
-        s = assign_impl(codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream, it > 0, &link);
+        BucketLink link = bucket_request(opt, N, M, K);
+        s = assign_impl(opt, c, codes, N, M, centers, K, tables, assign, nullptr, workspace, (hipStream_t)stream, it > 0,
+                        &link);
         if (s != PQKM_OK) return s;
-        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream, &link);
+        s = update_impl(opt, c, codes, N, M, assign, K, tables, centers, hist, counts, workspace, (hipStream_t)stream,
+                        &link);
         if (s != PQKM_OK) return s;
     }
     return PQKM_OK;
@@ -921,12 +954,13 @@ pqkm_status pqkm_fit_until(const uint8_t* codes, int64_t N, int32_t M, const flo
         unsigned fb = (unsigned)((N + 255) / 256 < 65536 ? (N + 255) / 256 : 65536);
         hipLaunchKernelGGL(fill_i32_kernel, dim3(fb), dim3(256), 0, st, prev, N, (int32_t)-1);
     }
+    const Options opt = options_snapshot();
     for (int it = 0; it < max_iters; ++it) {
-        BucketLink link = bucket_request(N, M, K);
-        s = assign_impl(codes, N, M, centers, K, tables, assign, dist, workspace, st, it > 0, &link);
+        BucketLink link = bucket_request(opt, N, M, K);
+        s = assign_impl(opt, c, codes, N, M, centers, K, tables, assign, dist, workspace, st, it > 0, &link);
         if (s != PQKM_OK) return s;
         hipLaunchKernelGGL(iter_assign_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, assign, prev, dist, N, pa);
-        s = update_impl(codes, N, M, assign, K, tables, centers, hist, counts, workspace, st, &link);
+        s = update_impl(opt, c, codes, N, M, assign, K, tables, centers, hist, counts, workspace, st, &link);
         if (s != PQKM_OK) return s;
         hipLaunchKernelGGL(iter_hist_stats_kernel, dim3(STAT_BLOCKS), dim3(256), 0, st, hist, (int64_t)K * M * L,
                            counts, K, ph);
@@ -961,11 +995,8 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
     } else if (strcmp(name, "hist_kernel") == 0) {
         if (value < 0 || value > 3) return PQKM_ERR_SHAPE;
         g_opt.hist_kernel = value;
-    } else if (strcmp(name, "hist_groups") == 0) {
-        if (value < 1 || value > 255) return PQKM_ERR_SHAPE;
-        g_hist_groups = value;
     } else if (strcmp(name, "profile") == 0) {
-        if (value < 0 || value > 1) return PQKM_ERR_SHAPE;
+        if (value < 0 || value > 3) return PQKM_ERR_SHAPE;
         g_opt.profile = value;
     } else if (strcmp(name, "launch_codes_log2") == 0) {
         if (value < 10 || value > 40) return PQKM_ERR_SHAPE;
@@ -978,19 +1009,12 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
 
 pqkm_status pqkm_profile_read(double* total_ms, int64_t* launches)
 {
-    if (!total_ms || !launches) return PQKM_ERR_NULL;
-    std::lock_guard<std::mutex> lk(g_mu);
-    double tot = 0.0;
-    for (size_t i = 0; i < g_used; ++i) {
-        if (hipEventSynchronize(g_pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) != hipSuccess) return PQKM_ERR_DEVICE;
-        tot += ms;
-    }
-    *total_ms = tot;
-    *launches = (int64_t)g_used;
-    g_used = 0;
-    return PQKM_OK;
+    return log_read(g_scan_log, total_ms, launches);
+}
+
+pqkm_status pqkm_profile_read_steps(double* total_ms, int64_t* steps)
+{
+    return log_read(g_step_log, total_ms, steps);
 }
 
 }  // extern "C"

@@ -2339,8 +2339,11 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
             for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
             if (m == 0 && lane == 0) counts[c0 + c] = cnt;
             if (cnt == 0) continue;                                          // empty cluster keeps its code
-            float b = v[q].x;
-            int bi = lane * 4;
+            // Eq. 8's argmin as a sequential scan reads it: start from +inf, strict "<" over ascending l, so a
+            // candidate whose sum is NaN or +inf is never taken and candidate 0 remains if none is
+            float b = INFINITY;
+            int bi = IDX_NONE;
+            if (v[q].x < b) { b = v[q].x; bi = lane * 4; }
             if (v[q].y < b) { b = v[q].y; bi = lane * 4 + 1; }
             if (v[q].z < b) { b = v[q].z; bi = lane * 4 + 2; }
             if (v[q].w < b) { b = v[q].w; bi = lane * 4 + 3; }
@@ -2350,7 +2353,7 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
                 const int oi = __shfl_xor(bi, d);
                 if (ob < b || (ob == b && oi < bi)) { b = ob; bi = oi; }
             }
-            if (lane == 0) centers[pair] = (uint8_t)bi;
+            if (lane == 0) centers[pair] = (uint8_t)(bi == IDX_NONE ? 0 : bi);
         }
     }
 }

@@ -379,6 +379,91 @@ def test_update_empty_input_and_big_counts(env):
     np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
 
 
+def test_vote_is_fused_on_a_vote_whose_winner_depends_on_it(env):
+    """Eq. 8 as read here accumulates with ONE fused multiply-add per non-zero bin.  Constructed two-bin votes
+    (bin 5 holds one member, bin 9 holds h2) for which a separate multiply and add would pick another candidate,
+    run through pqkm_update: the centers must be the oracle's, which is pinned to the fused reading on the CPU."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(6)
+    cases = []
+    while len(cases) < 6:
+        a1 = np.float32(rng.random() * 1000 + 1)
+        a2 = np.float32(rng.random() * 10 + 0.01)
+        h2 = int(rng.integers(3, 1000))
+        u = np.float32(np.float32(np.float32(h2) * a2) + a1)                       # multiply, round, add, round
+        f = np.float32(np.float64(h2) * np.float64(a2) + np.float64(a1))            # exact product and sum in fp64
+        if f != u:
+            cases.append((a1, a2, h2, f, u))
+    K, M = len(cases), 1
+    tables = np.full((M, 256, 256), 1e9, np.float32)
+    codes, assign = [], []
+    for k, (a1, a2, h2, f, u) in enumerate(cases):
+        # cluster k's candidates live in columns 2k (lx) and 2k + 1 (ly) ... but one table serves all clusters, so
+        # every cluster gets its own pair of member bins as well: bins 2k and 2k + 1
+        jb1, jb2 = 2 * k, 2 * k + 1
+        lx, ly = (100 + 2 * k + 1, 100 + 2 * k) if f < u else (100 + 2 * k, 100 + 2 * k + 1)
+        tables[0, jb1, lx], tables[0, jb2, lx] = a1, a2
+        tables[0, jb1, ly], tables[0, jb2, ly] = (max(f, u) if f < u else min(f, u)), 0.0
+        codes += [[jb1]] + [[jb2]] * h2
+        assign += [k] * (1 + h2)
+    codes = np.array(codes, np.uint8)
+    assign = np.array(assign, np.int32)
+    cent0 = np.zeros((K, M), np.uint8)
+    rc, rh, rcnt = oracle.update(codes, assign, tables, cent0)
+    fused_differs = 0
+    for k, (a1, a2, h2, f, u) in enumerate(cases):
+        lx, ly = (100 + 2 * k + 1, 100 + 2 * k) if f < u else (100 + 2 * k, 100 + 2 * k + 1)
+        assert rc[k, 0] == (lx if f < u else ly)             # the fused winner; unfused would tie -> lower index
+        fused_differs += rc[k, 0] != min(lx, ly)
+    assert fused_differs >= 1
+    for hk in (0, 1, 2, 3):
+        pq.set_option("hist_kernel", hk)
+        try:
+            d_cent = _dev(env, cent0)
+            _, hist, counts = pq.update(_dev(env, codes), _dev(env, assign), _dev(env, tables), d_cent)
+            _sync(env)
+        finally:
+            pq.set_option("hist_kernel", 0)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
+@pytest.mark.parametrize("M", [4, 8, 16, 32, 5])
+def test_non_finite_table_entries(env, M):
+    """User tables with +inf, -inf and NaN entries.  Comparisons are IEEE "<" in a sequential scan: a NaN or +inf
+    sum is never selected (if none is, the result is index 0), -inf wins at the lowest index holding it.  Both
+    argmins (Eq. 5 over centers, Eq. 8 over candidates) must agree with the oracle's sequential scan."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(40 + M)
+    N, K = 6001, 150
+    codes = rng.integers(0, 256, size=(N, M), dtype=np.uint8)
+    centers = rng.integers(0, 256, size=(K, M), dtype=np.uint8)
+    for kind in ("nan", "mixed", "all_nan"):
+        tables = rand_tables(rng, M)
+        flat = tables.reshape(-1)
+        if kind == "nan":
+            flat[rng.choice(flat.size, flat.size // 50, replace=False)] = np.nan
+        elif kind == "mixed":
+            idx = rng.choice(flat.size, flat.size // 20, replace=False)
+            flat[idx[0::3]] = np.nan
+            flat[idx[1::3]] = np.inf
+            flat[idx[2::3]] = -np.inf
+        else:
+            flat[:] = np.nan
+        a, d = pq.assign(_dev(env, codes), _dev(env, centers), _dev(env, tables))
+        _sync(env)
+        ra, rd = oracle.assign(codes, centers, tables)
+        np.testing.assert_array_equal(a.cpu().numpy(), ra)
+        np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+        d_cent = _dev(env, centers)
+        _, hist, counts = pq.update(_dev(env, codes), a, _dev(env, tables), d_cent)
+        _sync(env)
+        rc, rh, rcnt = oracle.update(codes, ra, tables, centers)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
 # ------------------------------------------------------------------------------------ Alg. 1 on the configs
 def _run_config_full(env, cfg, iters, **over):
     """Every iteration compared in full: assign, dist, hist, counts, centers."""
@@ -515,10 +600,36 @@ def test_fit_until_matches_oracle(env, cfg, over):
     assert s3 == [] and (d3.cpu().numpy() == cent0).all()
 
 
-def _run_config_sampled(env, cfg, n_sample, iters=1, **over):
+def _check_every_element_written_and_consistent(env, d_codes, cent, tables, a, d, label):
+    """Every output element of a full-size assignment, on the host: none keeps its pre-filled value (-1 / NaN), every
+    assignment names a center, and dist[n] is bit for bit Eq. 3 for (codes[n], centers[assign[n]]) -- so each
+    element was written, to its own position, from its own code.  (That the center is the NEAREST one is what
+    the sampled comparison against the oracle's scan checks.)"""
+    oracle, torch = env["oracle"], env["torch"]
+    N, K = a.numel(), cent.shape[0]
+    assert int(a.min()) >= 0 and int(a.max()) < K, "an assignment was never written or is out of range"
+    assert not bool(torch.isnan(d).any()), "a distance was never written"
+    chunk = 50_000_000
+    starts = list(range(0, N, chunk))
+    if len(starts) > 24:                             # beyond 2**32 codes: the first, the last and every eighth stretch
+        starts = sorted(set(starts[::8]) | {starts[0], starts[-1]})
+    for n0 in starts:
+        n1 = min(N, n0 + chunk)
+        h_codes = d_codes[n0:n1].cpu().numpy()
+        h_a = a[n0:n1].cpu().numpy()
+        want = oracle.sdc_pairs(h_codes, cent[h_a], tables)
+        got = d[n0:n1].cpu().numpy()
+        bad = np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))
+        assert bad.size == 0, f"{label}: dist[{n0 + bad[0]}] is not the distance to its assigned center"
+        progress(f"{label}: distances of codes {n0}..{n1} are those of their assigned centers")
+
+
+def _run_config_sampled(env, cfg, n_sample, iters=1, full_first=False, **over):
     """Full-size run in the launch configuration the benchmark uses.  The assignment is checked
-    on a seeded sample of codes against all K centers; histogram, counts and vote are checked in
-    full by giving the GPU's assignment to the oracle."""
+    on a seeded sample of codes against all K centers (with full_first, the first iteration against the
+    oracle's scan over ALL codes) and, for every code, for having been written and being consistent with
+    its own distance; histogram, counts and vote are checked in full by giving the GPU's assignment to the
+    oracle."""
     pq, oracle, W, torch, dev = env["pq"], env["oracle"], env["W"], env["torch"], env["dev"]
     w = workload(cfg, **over)
     cw = W.codewords(w)
@@ -543,14 +654,25 @@ def _run_config_sampled(env, cfg, n_sample, iters=1, **over):
     counts = torch.empty(w.K, dtype=torch.int32, device=dev)
     for it in range(iters):
         progress(f"config {cfg}: iteration {it + 1} assign on the GPU")
+        a.fill_(-1)                                  # an element the scan never writes must not pass
+        d.fill_(float("nan"))
         pq.assign(d_codes, d_cent, tables_d, assign=a, dist=d, workspace=ws)
         _sync(env)
-        progress(f"config {cfg}: oracle on {n_sample} sampled codes x {w.K} centers")
-        ra, rd = oracle.assign(s_codes, cent, tables)
-        idx = torch.from_numpy(sample).to(dev)
-        np.testing.assert_array_equal(a[idx].cpu().numpy(), ra)
-        np.testing.assert_array_equal(d[idx].cpu().numpy().view(np.uint32), rd.view(np.uint32))
-        assert int(a.min()) >= 0 and int(a.max()) < w.K
+        if full_first and it == 0:
+            progress(f"config {cfg}: oracle scan over all {w.N} codes x {w.K} centers")
+            h_codes = d_codes.cpu().numpy()
+            ra, rd = oracle.assign(h_codes, cent, tables)
+            del h_codes
+            np.testing.assert_array_equal(a.cpu().numpy(), ra)
+            np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+            del ra, rd
+        else:
+            progress(f"config {cfg}: oracle on {n_sample} sampled codes x {w.K} centers")
+            ra, rd = oracle.assign(s_codes, cent, tables)
+            idx = torch.from_numpy(sample).to(dev)
+            np.testing.assert_array_equal(a[idx].cpu().numpy(), ra)
+            np.testing.assert_array_equal(d[idx].cpu().numpy().view(np.uint32), rd.view(np.uint32))
+            _check_every_element_written_and_consistent(env, d_codes, cent, tables, a, d, f"config {cfg} iteration {it + 1}")
         progress(f"config {cfg}: update on the GPU")
         pq.update(d_codes, a, tables_d, d_cent, hist=hist, counts=counts, workspace=ws)
         _sync(env)
@@ -565,8 +687,10 @@ def _run_config_sampled(env, cfg, n_sample, iters=1, **over):
         progress(f"config {cfg}: iteration {it + 1} bit-exact (assign sampled, update full)")
 
 
-def test_config3_sift64_sampled(env):
-    _run_config_sampled(env, 3, 100_000, iters=2)
+def test_config3_sift64_first_iteration_full_then_sampled(env):
+    """Iteration 1 against the oracle's scan over all 1e7 codes (1e11 evaluations on the host cores), iteration 2
+    sampled; the update of both in full."""
+    _run_config_sampled(env, 3, 100_000, iters=2, full_first=True)
 
 
 def test_config4_cnn_sampled(env):
