@@ -53,7 +53,8 @@ typedef enum {
     PQKM_ERR_NULL = 1,      /* a required pointer is NULL                                  */
     PQKM_ERR_SHAPE = 2,     /* N < 0, K < 1, M < 1 or M > 64, Ds < 1, iters < 0, bad align */
     PQKM_ERR_WORKSPACE = 3, /* workspace NULL / misaligned / smaller than required         */
-    PQKM_ERR_DEVICE = 4     /* not a gfx950 device, or a HIP call failed                   */
+    PQKM_ERR_DEVICE = 4,    /* not a gfx950 device, or a HIP call failed                   */
+    PQKM_ERR_TOO_LARGE = 5  /* pqkm_assign_noalloc: the problem exceeds its static scratch */
 } pqkm_status;
 
 /* Static, NUL-terminated description of a status code. */
@@ -108,6 +109,24 @@ pqkm_status pqkm_decode(const uint8_t *codes, int64_t N, int32_t M, int32_t Ds, 
 pqkm_status pqkm_assign(const uint8_t *codes, int64_t N, int32_t M, const uint8_t *centers,
                         int32_t K, const float *tables, int32_t *assign, float *dist,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * pqkm_assign for callers that can neither allocate device memory nor hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as pqkm_assign, but the scratch is a static device array inside the library
+ * (PQKM_NOALLOC_SCRATCH_BYTES per GPU, held from library load until the process ends), so the call allocates
+ * and frees nothing and takes no workspace argument.
+ *   - Limit: pqkm_workspace_bytes(N, M, K) <= PQKM_NOALLOC_SCRATCH_BYTES, else PQKM_ERR_TOO_LARGE and
+ *     nothing is launched (64 MiB cover e.g. N = 1e6 four-byte codes against K = 1000 centers).
+ *   - Every call on a GPU shares that GPU's array: two calls that overlap in time on one GPU (different
+ *     streams, or threads) race and give undefined results.  Calls in stream order are fine; nothing needs
+ *     clearing between them (the kernels initialise what they read).
+ *   - The "profile" option of pqkm_tuning.h is ignored here (its events are created on demand).
+ */
+#define PQKM_NOALLOC_SCRATCH_BYTES (64u * 1024u * 1024u)
+pqkm_status pqkm_assign_noalloc(const uint8_t *codes, int64_t N, int32_t M, const uint8_t *centers,
+                                int32_t K, const float *tables, int32_t *assign, float *dist,
+                                void *stream);
 
 /*
  * Update step by sparse voting (Eq. 7 then Eq. 8):

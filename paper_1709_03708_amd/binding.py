@@ -34,6 +34,7 @@ def load():
         lib.pqkm_workspace_bytes.argtypes = [i64, i32, i32]
         lib.pqkm_build_tables.argtypes = [vp, i32, i32, vp, vp]
         lib.pqkm_assign.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.pqkm_assign_noalloc.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp]
         lib.pqkm_update.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.pqkm_fit.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.pqkm_fit_until_workspace_bytes.restype = sz
@@ -45,7 +46,7 @@ def load():
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         lib.pqkm_profile_read_steps.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
-        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
+        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_assign_noalloc", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
                   "pqkm_profile_read", "pqkm_profile_read_steps", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -156,6 +157,26 @@ def assign(codes, centers, tables, assign=None, dist=None, want_dist=True, works
     workspace, wb = _ws(workspace, N, M, K, codes.device)
     _check(load().pqkm_assign(_ptr(codes), N, M, _ptr(centers), K, _ptr(tables), _ptr(assign), _ptr(dist),
                               _ptr(workspace), wb, _stream()), "pqkm_assign")
+    return assign, dist
+
+
+NOALLOC_SCRATCH_BYTES = 64 * 1024 * 1024
+
+
+def assign_noalloc(codes, centers, tables, assign, dist=None):
+    """pqkm_assign_noalloc: outputs are the caller's, the scratch is the library's static device array; raises
+    PqkmError (code 5) when pqkm_workspace_bytes(N, M, K) exceeds NOALLOC_SCRATCH_BYTES.  -> (assign, dist)."""
+    import torch
+
+    N, M = codes.shape
+    K = centers.shape[0]
+    _need(codes, torch.uint8, (N, M), "codes")
+    _need(centers, torch.uint8, (K, M), "centers")
+    _need(tables, torch.float32, (M, L, L), "tables")
+    _need(assign, torch.int32, (N,), "assign")
+    _need(dist, torch.float32, (N,), "dist")
+    _check(load().pqkm_assign_noalloc(_ptr(codes), N, M, _ptr(centers), K, _ptr(tables), _ptr(assign), _ptr(dist),
+                                      _stream()), "pqkm_assign_noalloc")
     return assign, dist
 
 

@@ -12,6 +12,10 @@
 
 #include "pqkm_kernels.h"
 
+// Scratch of pqkm_assign_noalloc: one array per GPU, held from the moment the library is loaded on it until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address to pass on.
+static __device__ __align__(256) unsigned char scratch[PQKM_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace pqkm;
@@ -184,6 +188,26 @@ pqkm_status check_device()
     if (hipGetDeviceProperties(&p, dev) != hipSuccess) return PQKM_ERR_DEVICE;
     if (strncmp(p.gcnArchName, "gfx950", 6) != 0) return PQKM_ERR_DEVICE;
     checked_dev = dev;
+    return PQKM_OK;
+}
+
+// Device address of `scratch` on the current device: asked of the runtime once per device (each GPU holds its own
+// copy at its own address) and kept.
+constexpr int SCRATCH_MAX_DEVICES = 64;
+void* g_scratch_ptr[SCRATCH_MAX_DEVICES];
+std::mutex g_scratch_mu;
+
+pqkm_status scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_DEVICES) return PQKM_ERR_DEVICE;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PQKM_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return PQKM_OK;
 }
 
@@ -776,6 +800,7 @@ const char* pqkm_status_string(pqkm_status s)
         case PQKM_ERR_SHAPE: return "invalid shape, size, alignment or option";
         case PQKM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case PQKM_ERR_DEVICE: return "not a gfx950 device, or a HIP call failed";
+        case PQKM_ERR_TOO_LARGE: return "problem needs more scratch than the static buffer of pqkm_assign_noalloc holds";
     }
     return "unknown status";
 }
@@ -847,6 +872,22 @@ pqkm_status pqkm_assign(const uint8_t* codes, int64_t N, int32_t M, const uint8_
     if ((s = check_device()) != PQKM_OK) return s;
     return assign_impl(options_snapshot(), c, codes, N, M, centers, K, tables, assign, dist, workspace,
                        (hipStream_t)stream);
+}
+
+pqkm_status pqkm_assign_noalloc(const uint8_t* codes, int64_t N, int32_t M, const uint8_t* centers, int32_t K,
+                                const float* tables, int32_t* assign, float* dist, void* stream)
+{
+    if (!shape_ok(N, M, K)) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    const Carve c = carve(N, M, K);
+    if (c.total > (size_t)PQKM_NOALLOC_SCRATCH_BYTES) return PQKM_ERR_TOO_LARGE;
+    pqkm_status s = check_device();
+    if (s != PQKM_OK) return s;
+    void* ws = nullptr;
+    if ((s = scratch_of_current_device(&ws)) != PQKM_OK) return s;
+    Options opt = options_snapshot();
+    opt.profile = 0;                        // the event pairs of the profile option are created on demand
+    return assign_impl(opt, c, codes, N, M, centers, K, tables, assign, dist, ws, (hipStream_t)stream);
 }
 
 pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,

@@ -37,8 +37,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    seen = {lib.pqkm_status_string(i).decode() for i in range(5)}
-    assert len(seen) == 5 and "ok" in seen
+    seen = {lib.pqkm_status_string(i).decode() for i in range(6)}
+    assert len(seen) == 6 and "ok" in seen
     assert lib.pqkm_status_string(99).decode() == "unknown status"
 
 

@@ -684,7 +684,8 @@ def _run_config_sampled(env, cfg, n_sample, iters=1, full_first=False, **over):
         np.testing.assert_array_equal(u32(counts), rcnt)
         np.testing.assert_array_equal(u32(hist), rh)
         np.testing.assert_array_equal(d_cent.cpu().numpy(), cent)
-        progress(f"config {cfg}: iteration {it + 1} bit-exact (assign sampled, update full)")
+        how = "in full" if full_first and it == 0 else "sampled, every element self-consistent"
+        progress(f"config {cfg}: iteration {it + 1} bit-exact (assign {how}, update full)")
 
 
 def test_config3_sift64_first_iteration_full_then_sampled(env):
