@@ -177,12 +177,21 @@ def microbench(torch) -> int:
     return 0
 
 
+_T0 = time.perf_counter()
+
+
+def note(msg: str) -> None:
+    """Progress on stderr (stdout carries the one JSON line): a long run must not look hung."""
+    print(f"bench.py [{time.perf_counter() - _T0:6.1f} s] {msg}", file=sys.stderr, flush=True)
+
+
 def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.0):
     """Generate configuration `cfg`, run `warmup` untimed and `steps` timed iterations, and return the figures
     (or None if the projected total would pass the time budget).  The scan kernel and the whole assignment
     steps are timed by HIP event pairs the library records on the stream it launches on."""
     w = W.CONFIGS[cfg]
     N, M, K = w.N, w.M, w.K
+    note(f"configuration {cfg}: generating {N} codes of {M} bytes on the GPU")
     tables = pq.build_tables(torch.from_numpy(W.codewords(w)).to(dev))
     codes = W.codes_torch(w, dev)
     init_idx = W.init_center_indices(w)
@@ -191,8 +200,10 @@ def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.
     assign = torch.empty(N, dtype=torch.int32, device=dev)
     ws = torch.empty(pq.workspace_bytes(N, M, K), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
+    short = float(N) * K * M <= 2e12
+    talk = float(N) * K * M >= 1e14                  # iterations of seconds: wait for each and say so
 
-    def run(n: int) -> int:
+    def run(n: int, what: str = "") -> int:
         """`n` iterations as pqkm_fit calls of w.iters iterations, each from the initial centers."""
         calls, left = 0, n
         while left > 0:
@@ -201,9 +212,11 @@ def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.
             pq.fit(codes, tables, centers, it, assign=assign, workspace=ws)
             left -= it
             calls += 1
+            if talk:
+                torch.cuda.synchronize()
+                note(f"configuration {cfg}: {what} iteration {n - left} of {n} done")
         return calls
 
-    short = float(N) * K * M <= 2e12
     # The GPU raises its clocks only after some tens of milliseconds of load: a handful of sub-millisecond warm-up
     # steps would leave the timed region on the ramp.  Workloads whose iteration is short are therefore run untimed
     # for a fixed wall time first (the W warm-up steps then follow as asked).
@@ -240,7 +253,7 @@ def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.
         pq.set_option("profile", 3)
         if warmup > 0:
             tw = time.perf_counter()
-            run(1)
+            run(1, "warm-up")
             torch.cuda.synchronize()
             one = time.perf_counter() - tw
             if budget > 0 and t_start is not None:
@@ -250,12 +263,12 @@ def measure(args, cfg, steps, warmup, pq, W, torch, dev, t_start=None, budget=0.
                     pq.profile_read()
                     pq.profile_read_steps()
                     return {"skipped": True, "first_step_s": one, "projected_s": projected}
-            run(warmup - 1)
+            run(warmup - 1, "warm-up")
             torch.cuda.synchronize()
         pq.profile_read()                               # discard the warm-up launches
         pq.profile_read_steps()
         t0 = time.perf_counter()
-        fit_calls = run(steps)
+        fit_calls = run(steps, "timed")
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     scan_ms_total, scan_launches = pq.profile_read()
@@ -294,6 +307,7 @@ def cpu_baseline(r, oracle) -> dict:
     cores = oracle.max_threads()
 
     def timed(threads: int, seconds: float):
+        note(f"CPU oracle on {threads} thread(s), about {seconds:.0f} s")
         oracle.set_threads(threads)
         n_sub = int(min(w.N, max(2_000, seconds * 1e8 * threads / K)))
         h_codes = r["codes"][:n_sub].cpu().numpy()

@@ -85,12 +85,15 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
-        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, pool_off, bseg_off, total;
+        gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, pool_off, bseg_off, skew_off,
+        total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
 constexpr int64_t GROUP_CHUNK_MAX = (int64_t)1 << 26;
 inline int64_t group_alloc(int64_t n) { return (n + 14) & ~(int64_t)7; }   // regrouped positions for n codes
+constexpr int SW_C_MAX = 256 * 16;          // most codes a workgroup of the sliding-window scan takes
+inline int64_t sw_alloc(int64_t n) { return ((n + SW_C_MAX - 1) / SW_C_MAX + 1) * SW_C_MAX; }   // whole workgroups of any shape
 
 // Shape of the LDS-privatised histogram pass: KT clusters per workgroup, `groups` cluster groups, S code slices.
 struct HistPlan { int KT; int64_t groups; int S; bool cheap; };
@@ -122,6 +125,11 @@ Carve carve(int64_t N, int M, int K)
         int TK = 128 / M;
         size_t ntiles = ((size_t)K + TK - 1) / TK;
         c.img_bytes = ntiles * (size_t)TILE_BYTES;
+        // the sliding-window scan of the wide codes tiles the centers 16 at a time (M planes of 16 KB per tile)
+        if (M >= 16) {
+            const size_t wide = (((size_t)K + 15) / 16) * (size_t)M * 16384;
+            if (wide > c.img_bytes) c.img_bytes = wide;
+        }
     }
     off += align256(c.img_bytes);
     c.hist_off = off;
@@ -172,6 +180,12 @@ Carve carve(int64_t N, int M, int K)
         c.plan8_off = off;
         off += align256(sizeof(GroupPlan8));
     }
+    // subcode words of the sliding-window scan (M = 16, 32): M/4 + 1 words per code position of one launch
+    c.skew_off = off;
+    if (M == 16 || M == 32) {
+        const int64_t na = sw_alloc(N < GROUP_CHUNK_MAX ? N : GROUP_CHUNK_MAX);
+        off += align256((size_t)na * (size_t)(M / 4 + 1) * sizeof(uint32_t));
+    }
     c.total = off;
     return c;
 }
@@ -221,6 +235,19 @@ pqkm_status check_workspace(const void* ws, size_t bytes, size_t need)
     if (need == 0) return PQKM_OK;
     if (ws == nullptr || ((uintptr_t)ws & 255) != 0 || bytes < need) return PQKM_ERR_WORKSPACE;
     return PQKM_OK;
+}
+
+// compute units of the current device (asked once; 256 if the query fails)
+int cu_count()
+{
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        return v;
+    }();
+    return n;
 }
 
 // ------------------------------------------------------------------ scan launch
@@ -292,19 +319,49 @@ template <int M>
 void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* img, const float4* rows, int ntiles,
                    int32_t* assign, float* dist, hipStream_t st);
 
-// M = 4 scans over regrouped codes: variants 70..79
-// compute units of the current device (asked once; 256 if the query fails)
-int cu_count()
+// Sliding-window scan of the wide codes (variants 50..59): the subcode words of this launch, then the scan.
+// R codes per lane-slot (a workgroup takes 256 R codes); variant 50 chooses R from the number of rounds:
+// a launch costs about rounds * (R + 5.5) (R codes' reads per phase, a 64 KB fill worth 4 and two barriers).
+inline int sw_codes_per_slot(int variant, int64_t n)
 {
-    static const int n = [] {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-            v = 256;
-        return v;
-    }();
-    return n;
+    if (variant == 51) return 16;
+    if (variant == 52) return 8;
+    const int ncu = cu_count();
+    static const int cand[] = {16, 8};
+    int best = 16;
+    double best_cost = 1e300;
+    for (int R : cand) {
+        const int64_t wgs = (n + 256 * R - 1) / (256 * R);
+        const double cost = (double)((wgs + ncu - 1) / ncu) * (R + 5.5);
+        if (cost < best_cost) { best_cost = cost; best = R; }
+    }
+    return best;
 }
+
+template <int M>
+pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_t* S, const float4* img, int ntiles16,
+                           int32_t* assign, float* dist, hipStream_t st)
+{
+    const int R = sw_codes_per_slot(variant, N);
+    const int64_t C = 256 * (int64_t)R;
+    const int64_t nwg = (N + C - 1) / C;
+    const int64_t n_alloc = nwg * C;
+    hipLaunchKernelGGL((code_skew_kernel<M>), dim3((unsigned)((n_alloc + 255) / 256)), dim3(256), 0, st, codes, N, S,
+                       n_alloc);
+    switch (R) {
+        case 8:
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 8, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
+                               n_alloc, img, ntiles16, assign, dist);
+            break;
+        default:
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
+                               n_alloc, img, ntiles16, assign, dist);
+            break;
+    }
+    return launched();
+}
+
+// M = 4 scans over regrouped codes: variants 70..79
 
 // Codes per lane-slot R of the 512-thread half-plane scan (a workgroup takes 128 R codes, one workgroup per
 // compute unit at a time).  The time of a launch is about rounds * (R + 7) with rounds = ceil(workgroups / CUs):
@@ -522,10 +579,11 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
         return variant;
     }
     if ((M == 16 || M == 32) && variant == 0) {
-        // the same for the wider codes (M = 16: 270, 343, 440, 524 us; M = 32: 640, 690, -, 1066 us)
+        // the same for the wider codes (M = 16: 270, 343, 440, 524 us; M = 32: 640, 690, -, 1066 us); beyond one
+        // round of those workgroups the sliding-window scan, whose workgroups take 2048 or 4096 codes
         const int64_t ncu = cu_count();
-        if (M == 16) return N <= ncu * 512 ? 7 : N <= ncu * 1024 ? 6 : N <= ncu * 1536 ? 2 : 0;
-        return N <= ncu * 512 ? 6 : N <= ncu * 1024 ? 2 : 0;
+        if (M == 16) return N <= ncu * 512 ? 7 : N <= ncu * 1024 ? 6 : N <= ncu * 1536 ? 2 : 50;
+        return N <= ncu * 512 ? 6 : N <= ncu * 1024 ? 2 : 50;
     }
     if (M == 4 && !img32 && special) return 34;
     if (M != 4 || variant != 0) return variant;
@@ -545,6 +603,7 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     return 70;                            // regrouped half-plane scan, codes per lane-slot chosen per launch
 }
 inline bool variant_grouped(int M, int variant) { return (M == 4 || M == 8) && variant >= 70 && variant <= 79; }
+inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) && variant >= 50 && variant <= 59; }
 
 // The fused iteration's hand-over from the scan to the histogram: filled in by the caller (wanted, KT, ngroups),
 // completed by the assignment (produced, nwg) when the scan that ran could file its codes by cluster group.
@@ -563,7 +622,14 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
     const int variant = effective_variant(M, opt.scan_variant, N, K, codes);
     const int layout = variant_layout(M, variant);
-    if (layout == 2 && M == 4)
+    const bool sliding = variant_sliding(M, variant);
+    if (sliding) {
+        // tiles of 16 centers, plane-ordered: img[tile][m][x][16]
+        ntiles = ((int64_t)K + 15) / 16;
+        total = ntiles * (int64_t)16 * M * L;
+        hipLaunchKernelGGL((tile_image_kernel<M, 0, 16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           centers, K, tables, img, total);
+    } else if (layout == 2 && M == 4)
         hipLaunchKernelGGL((tile_image_kernel<4, 2>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            centers, K, tables, img, total, reinterpret_cast<float*>(ws + c.rows_off));
     else if (layout == 1)
@@ -577,7 +643,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t per_launch = opt.launch_codes;
     // a little below the limit: with its padding a launch of exactly 2^26 codes needs one workgroup more than
     // 64 full rounds of 4096-code workgroups, and that workgroup would run a round of its own
-    if (grouped && per_launch > GROUP_CHUNK_MAX - 16384) per_launch = GROUP_CHUNK_MAX - 16384;
+    if ((grouped || sliding) && per_launch > GROUP_CHUNK_MAX - 16384) per_launch = GROUP_CHUNK_MAX - 16384;
     const float4* rows = reinterpret_cast<const float4*>(ws + c.rows_off);
     uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
@@ -593,7 +659,14 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         }
         EventPair ev{};
         const bool prof = (opt.profile & 1) && log_begin(g_scan_log, st, &ev);
-        if (grouped && M == 8)
+        if (sliding) {
+            if constexpr (M == 16 || M == 32) {
+                if (launch_scan_sw<M>(variant, codes + n0 * M, cnt, reinterpret_cast<uint32_t*>(ws + c.skew_off),
+                                      reinterpret_cast<const float4*>(img), (int)ntiles, assign + n0,
+                                      dist ? dist + n0 : nullptr, st) != PQKM_OK)
+                    return PQKM_ERR_DEVICE;
+            }
+        } else if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                  assign + n0, dist ? dist + n0 : nullptr, st);
         else if (grouped && M == 4 && link && link->wanted && variant == 70 && N <= per_launch &&

@@ -1776,6 +1776,291 @@ __global__ __launch_bounds__(THREADS) void assign_scan_skew_kernel(const uint8_t
 }
 
 // ---------------------------------------------------------------------------------------------
+// Sliding-window skewed scan for wide codes, M = 16, 32 (CNN-feature codes; Sec. 4).
+//
+// A tile is TK = 16 centers, and its M subspace planes (img[tile][s][x][16 centers], 16 KB each) do not
+// fit the LDS together, so they pass through it: the LDS holds a ring of eight planes, interleaved per
+// subcode -- row (x, s) of 64 bytes at byte x*512 + (s mod 8)*64, so that a row's bank quarter is s mod 4
+// whatever x is -- and every phase four new planes replace the four oldest ones (64 KB per fill).  Per
+// code and lane the eight partial sums of Eq. 3 stay in registers across the phases and are added to in
+// ascending s, which keeps the bits of the sequential fp32 sum.
+//
+// Two lanes form a slot (one code) and own the row's four 16-byte pieces two each; a 16-lane LDS access
+// holds eight slots.  Slot class j = 0..3 runs j subspaces behind (it reads s = 4*phase + t - j in step t
+// of a phase), which puts the rows of the four classes in four different bank quarters, and of the two
+// slots of a class one reads its lanes' lower pieces first and the other the upper: sixteen different
+// 16-byte positions in every access, whatever the subcodes.  Because the ring holds three planes more
+// than a phase consumes, a slot that runs behind still finds its planes: the skew costs three steps per
+// code and TILE (35 steps for 32 subspaces: j steps of -0.0 reads before the first plane, 3 - j after the
+// last), not per fill.
+//
+// What a lane reads in a phase -- four subcodes of its code, shifted by its slot's j -- comes from an
+// array the host prepares once per launch (code_skew_kernel): S[phase][position] = those four bytes as one
+// word, four bytes per code and phase.  The address of a read is (byte << 9) + a per-lane constant of the
+// ring position.  Minimum tracking, tile prefetch and winner recovery are those of the other scans.
+// ---------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(256) void code_skew_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                        uint32_t* __restrict__ S, int64_t n_alloc)
+{
+    constexpr int NW = M / 4, NPH = M / 4 + 1;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_alloc) return;
+    const int j = (int)((n & 7) >> 1);                  // the slot class of this position
+    const int64_t src = n < N ? n : N - 1;              // positions past the end repeat the last code
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(codes + src * M);
+    uint32_t w[NW + 2];
+    w[0] = 0u;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w[i + 1] = cw[i];
+    w[NW + 1] = 0u;
+#pragma unroll
+    for (int ph = 0; ph < NPH; ++ph) {
+        // bytes 4 ph - j .. 4 ph - j + 3 of the code (zero outside it)
+        const unsigned long long pair = ((unsigned long long)w[ph + 1] << 32) | w[ph];
+        S[(size_t)ph * n_alloc + n] = (uint32_t)(pair >> (8 * (4 - j)));
+    }
+}
+
+template <int T_BYTE>
+__device__ __forceinline__ uint32_t sdwa_shl_byte(uint32_t sh, uint32_t v)
+{
+    uint32_t r;
+    if (T_BYTE == 0)
+        asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0"
+                     : "=v"(r) : "v"(sh), "v"(v));
+    else if (T_BYTE == 1)
+        asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
+                     : "=v"(r) : "v"(sh), "v"(v));
+    else if (T_BYTE == 2)
+        asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2"
+                     : "=v"(r) : "v"(sh), "v"(v));
+    else
+        asm volatile("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3"
+                     : "=v"(r) : "v"(sh), "v"(v));
+    return r;
+}
+
+template <int M, int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* __restrict__ codes, int64_t N,
+                                                                 const uint32_t* __restrict__ S, int64_t n_alloc,
+                                                                 const float4* __restrict__ img, int ntiles,
+                                                                 int32_t* __restrict__ assign,
+                                                                 float* __restrict__ dist)
+{
+    constexpr int TK = 16, LPS = 2, NPH = M / 4 + 1;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int PLANE_F4 = 1024;                    // float4 per plane (256 subcodes x 16 centers)
+    constexpr int NF = 4 * PLANE_F4 / THREADS;        // float4 per thread per fill (four planes)
+    constexpr int SD = 8;                             // codes whose subcode words are in flight ahead of their use
+    constexpr uint32_t PAD = TILE_BYTES;              // 256 bytes of -0.0 after the ring
+    static_assert(THREADS == 512, "the fill mapping assumes 512 threads");
+    static_assert(C % 8 == 0 && R % SD == 0, "slot classes repeat every 8 positions; the word ring holds SD codes");
+
+    __shared__ float4 tile[TILE_F4 + 16];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid & 1;
+    const int c = tid >> 1;
+    const int j = (c & 7) >> 1;                       // subspaces this slot runs behind
+    const int h = c & 1;                              // 1: the lanes read the upper of their two pieces first
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t nine = 9;
+
+    if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
+
+    // ring position constants: a read of ring slot e (subspace s = e mod 8 for a slot with j = 0) goes, for this
+    // lane, to ring slot (e - j) mod 8, piece 2q + h first
+    uint32_t uc[4], un[4];                            // current phase (e = t or 4 + t), next phase
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        uc[t] = (uint32_t)((t - j) & 7) * 64u + (uint32_t)(2 * q + h) * 16u;
+        un[t] = (uint32_t)((4 + t - j) & 7) * 64u + (uint32_t)(2 * q + h) * 16u;
+    }
+
+    float acc[R][8];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[r][i] = -0.0f;
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    // fill: element e = i*THREADS + tid of the four planes is (x = e >> 4, plane e >> 2 & 3, piece e & 3): the 16
+    // lanes of an LDS write cover four planes x four pieces of one x, sixteen different positions
+    const uint32_t lds_w = (uint32_t)(tid >> 4) * 512u + (uint32_t)((tid >> 2) & 3) * 64u + (uint32_t)(tid & 3) * 16u;
+    const uint32_t glb_r = (uint32_t)((tid >> 2) & 3) * 16384u + (uint32_t)(tid >> 4) * 64u + (uint32_t)(tid & 3) * 16u;
+    auto gload = [&](int64_t plane0, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)plane0 * PLANE_F4), 0, 4 * PLANE_F4 * 16, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, glb_r, i * 2048, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+    auto fill = [&](int half) {
+        char* dst = reinterpret_cast<char*>(tile) + lds_w + (uint32_t)half * 256u;
+#pragma unroll
+        for (int i = 0; i < NF; ++i) *reinterpret_cast<v4f*>(dst + i * 16384) = pf[i];
+    };
+
+    // subcode words: S[phase][base + r*SLOTS + c], read through a buffer descriptor of the workgroup's stretch of
+    // a phase (uniform base, one 32-bit lane offset, the code as a scalar offset: no 64-bit address per code)
+    const uint32_t word_off = (uint32_t)c * 4u;
+    auto wload = [&](const uint32_t* phase_words, int r) -> uint32_t {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(phase_words), 0, C * 4,
+                                                                      0x00020000);
+        return __builtin_amdgcn_raw_buffer_load_b32(rs, word_off, r * SLOTS * 4, 0);
+    };
+    const uint32_t* sp = S + base;
+    uint32_t sw[SD];
+#pragma unroll
+    for (int r = 0; r < SD; ++r) sw[r] = wload(sp, r);
+
+    struct Pair { float4 a, b; };
+
+    // One phase: KIND 0 = first of a tile (the slot's first j steps read -0.0), 1 = middle, 2 = last (3 steps; the
+    // steps past the slot's last subspace read -0.0; ends with the minimum update).  `next_words` = the words of
+    // the phase after this one; `pf_plane` >= 0: the four planes to prefetch for the next fill.
+    auto scan_phase = [&](auto kind_c, const uint32_t* next_words, int64_t pf_plane, int t_index) {
+        constexpr int KIND = decltype(kind_c)::value;
+        constexpr int NS = KIND == 2 ? 3 : 4;
+        auto issue = [&](int st) -> Pair {
+            const int r = st / NS, t = st % NS;
+            const uint32_t w = sw[r % SD];
+            uint32_t ad = (t == 0) ? sdwa_shl_byte<0>(nine, w) : (t == 1) ? sdwa_shl_byte<1>(nine, w)
+                        : (t == 2) ? sdwa_shl_byte<2>(nine, w) : sdwa_shl_byte<3>(nine, w);
+            ad += uc[t];
+            if (KIND == 0 && t < 3) ad = (j > t) ? PAD + (uc[t] & 255u) : ad;
+            if (KIND == 2) ad = (j > t) ? ad : PAD + (uc[t] & 255u);
+            Pair p;
+            p.a = lds_read16(tb, ad);
+            p.b = lds_read16(tb, ad ^ 16u);
+            return p;
+        };
+        Pair ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (KIND != 2) {
+#pragma unroll
+                for (int i = 0; i < NF; ++i)
+                    if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(pf_plane, i);
+            }
+#pragma unroll
+            for (int t = 0; t < NS; ++t) {
+                const int st = r * NS + t;
+                const Pair cur = ring[st % DEPTH];
+                if (st + DEPTH < R * NS) ring[st % DEPTH] = issue(st + DEPTH);
+                acc[r][0] += cur.a.x; acc[r][1] += cur.a.y; acc[r][2] += cur.a.z; acc[r][3] += cur.a.w;
+                acc[r][4] += cur.b.x; acc[r][5] += cur.b.y; acc[r][6] += cur.b.z; acc[r][7] += cur.b.w;
+                if (t == NS - 1) {
+                    // the word of code r is no longer needed (its last read was issued DEPTH steps ago)
+                    sw[r % SD] = (r + SD < R) ? wload(sp, r + SD) : wload(next_words, r + SD - R);
+                    if (KIND == 2) {
+                        float m8 = min3_f32(acc[r][0], acc[r][1], acc[r][2]);
+                        m8 = min3_f32(m8, acc[r][3], acc[r][4]);
+                        m8 = min3_f32(m8, acc[r][5], acc[r][6]);
+                        const float nb = min3_f32(m8, acc[r][7], best[r]);
+                        tix[r] = (nb < best[r]) ? t_index : tix[r];
+                        best[r] = nb;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[r][i] = -0.0f;
+                    }
+                }
+            }
+        }
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int64_t plane_t = (int64_t)t * M;
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        // phase 0: planes 0..3 into the lower half of the ring
+        __syncthreads();
+        fill(0);
+        __syncthreads();
+        sp = S + base;
+        scan_phase(std::integral_constant<int, 0>{}, sp + (size_t)n_alloc, plane_t + 4, t);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { const uint32_t x = uc[i]; uc[i] = un[i]; un[i] = x; }
+#pragma unroll 1
+        for (int ph = 1; ph < NPH - 1; ++ph) {
+            __syncthreads();
+            fill(ph & 1);
+            __syncthreads();
+            sp = S + (size_t)ph * n_alloc + base;
+            const uint32_t* nxt = S + (size_t)(ph + 1) * n_alloc + base;
+            const int64_t pfp = (ph + 1 < NPH - 1) ? plane_t + 4 * (ph + 1) : (int64_t)tn * M;
+            scan_phase(std::integral_constant<int, 1>{}, nxt, pfp, t);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { const uint32_t x = uc[i]; uc[i] = un[i]; un[i] = x; }
+        }
+        // last phase: no new planes; the slots that run behind finish their last subspaces
+        sp = S + (size_t)(NPH - 1) * n_alloc + base;
+        scan_phase(std::integral_constant<int, 2>{}, S + base, (int64_t)-1, t);
+    }
+
+    // Epilogue: the lanes holding their slot's minimum rebuild the sums of their 8 centers in the winning tile
+    // from the image in global memory (same bits, same order of additions), pick the lowest center attaining the
+    // minimum, and the two lanes of the slot are merged by (value, index).
+    const int p1 = 2 * q + h, p2 = p1 ^ 1;
+#pragma unroll 1
+    for (int r0 = 0; r0 < R; ++r0) {
+        float b = INFINITY;
+        int tx = -1;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r == r0) { b = best[r]; tx = tix[r]; }
+        const float smin = __builtin_fminf(b, __shfl_xor(b, 1));
+        const bool need = tx >= 0 && b == smin;
+        int bi = IDX_NONE;
+        float bv = INFINITY;
+        const int64_t n = base + (int64_t)r0 * SLOTS + c;
+        if (need) {
+            const int64_t nn = n < N ? n : N - 1;
+            const uint8_t* x = codes + nn * M;
+            const char* gbase = reinterpret_cast<const char*>(img + (size_t)tx * M * PLANE_F4);
+            v4f sa = *reinterpret_cast<const v4f*>(gbase + (uint32_t)x[0] * 64u + (uint32_t)p1 * 16u);
+            v4f sb = *reinterpret_cast<const v4f*>(gbase + (uint32_t)x[0] * 64u + (uint32_t)p2 * 16u);
+#pragma unroll 4
+            for (int s = 1; s < M; ++s) {
+                const char* row = gbase + (size_t)s * 16384 + (uint32_t)x[s] * 64u;
+                sa = sa + *reinterpret_cast<const v4f*>(row + (uint32_t)p1 * 16u);
+                sb = sb + *reinterpret_cast<const v4f*>(row + (uint32_t)p2 * 16u);
+            }
+            const int ka = tx * TK + p1 * 4, kb = tx * TK + p2 * 4;
+            int k = IDX_NONE;
+            if (sa.w == b) k = ka + 3;
+            if (sa.z == b) k = ka + 2;
+            if (sa.y == b) k = ka + 1;
+            if (sa.x == b) k = ka;
+            int k2 = IDX_NONE;
+            if (sb.w == b) k2 = kb + 3;
+            if (sb.z == b) k2 = kb + 2;
+            if (sb.y == b) k2 = kb + 1;
+            if (sb.x == b) k2 = kb;
+            bi = k < k2 ? k : k2;
+            bv = b;
+        }
+        {
+            const float ob = __shfl_xor(bv, 1);
+            const int oi = __shfl_xor(bi, 1);
+            if (ob < bv || (ob == bv && oi < bi)) { bv = ob; bi = oi; }
+        }
+        if (q == 0 && n < N) {
+            assign[n] = (bi == IDX_NONE) ? 0 : bi;
+            if (dist) dist[n] = bv;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Zero fill (a kernel, not a memset node, so that callers may capture the calls in a graph).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* __restrict__ p, int64_t n)

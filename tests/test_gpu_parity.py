@@ -194,7 +194,8 @@ def test_regrouped_scan_in_several_launches(env):
 
 @pytest.mark.parametrize("M,variant", [(8, 0), (8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (8, 6), (8, 7), (8, 10),
                                        (16, 0), (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 7), (16, 10),
-                                       (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 10)])
+                                       (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 10),
+                                       (16, 50), (16, 51), (16, 52), (32, 50), (32, 51), (32, 52)])
 def test_assign_every_compiled_shape_wide_codes(env, M, variant):
     w = workload(1, M=M, D=16 * M, N=7001, K=77, T=40)
     W = env["W"]
@@ -204,6 +205,38 @@ def test_assign_every_compiled_shape_wide_codes(env, M, variant):
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
     rng = np.random.default_rng(M + variant)
     _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=2, scan_variant=variant)
+
+
+@pytest.mark.parametrize("M", [16, 32])
+@pytest.mark.parametrize("variant", [51, 52])
+@pytest.mark.parametrize("N,K", [(1, 1), (9001, 16), (4097, 1000), (300_007, 333)])
+def test_assign_sliding_window_scan(env, M, variant, N, K):
+    """The sliding-window scan of the wide codes (16 centers per tile, planes passing through a ring in the LDS,
+    slot classes running 0..3 subspaces behind): ragged workgroups and tiles, one tile, many tiles; real tables,
+    non-symmetric tables, Hamming tables (massive ties, in and across tiles and lanes) and tables with NaN and
+    infinite entries; every result bit for bit."""
+    W = env["W"]
+    w = workload(1, M=M, D=16 * M, N=max(N, K), K=K, T=97)
+    allc = W.codes_numpy(w)
+    centers = allc[W.init_center_indices(w)].copy()
+    codes = allc[:N]
+    rng = np.random.default_rng(N + K + M + variant)
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+    if N <= 10_000:
+        _check_assign(env, codes, centers, rand_tables(rng, M), assign_kernel=2, scan_variant=variant)
+        ham = np.ones((M, 256, 256), np.float32)
+        for m in range(M):
+            np.fill_diagonal(ham[m], 0)
+        _check_assign(env, (codes % 3).astype(np.uint8), (centers % 3).astype(np.uint8), ham, assign_kernel=2,
+                      scan_variant=variant)
+        bad = rand_tables(rng, M)
+        flat = bad.reshape(-1)
+        idx = rng.choice(flat.size, flat.size // 20, replace=False)
+        flat[idx[0::3]] = np.nan
+        flat[idx[1::3]] = np.inf
+        flat[idx[2::3]] = -np.inf
+        _check_assign(env, codes, centers, bad, assign_kernel=2, scan_variant=variant)
 
 
 @pytest.mark.parametrize("M", [4, 8, 5, 16, 32])
