@@ -354,7 +354,7 @@ pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_
                                n_alloc, img, ntiles16, assign, dist);
             break;
         default:
-            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
                                n_alloc, img, ntiles16, assign, dist);
             break;
     }

@@ -1853,7 +1853,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
     constexpr int C = SLOTS * R;
     constexpr int PLANE_F4 = 1024;                    // float4 per plane (256 subcodes x 16 centers)
     constexpr int NF = 4 * PLANE_F4 / THREADS;        // float4 per thread per fill (four planes)
-    constexpr int SD = 8;                             // codes whose subcode words are in flight ahead of their use
+    constexpr int SD = R;                             // the words of a whole phase are loaded one phase ahead
     constexpr uint32_t PAD = TILE_BYTES;              // 256 bytes of -0.0 after the ring
     static_assert(THREADS == 512, "the fill mapping assumes 512 threads");
     static_assert(C % 8 == 0 && R % SD == 0, "slot classes repeat every 8 positions; the word ring holds SD codes");
