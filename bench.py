@@ -122,6 +122,52 @@ def naive_update_bench(args, w, pq, torch, dev) -> int:
     return 0
 
 
+def indexed_bench(args, w, pq, torch, dev) -> int:
+    """Alg. 1's two FindNN variants on a stretch of the configuration's codes against all its K centers: the linear
+    scan and the search through the exact index over the centers, timed with HIP events, and the verdict of
+    Check() (10 trials on 4096 sampled codes, as in Sec. 3.1)."""
+    import dataclasses
+
+    import workloads as W
+
+    n = min(w.N, args.indexed_codes)
+    wl = dataclasses.replace(w, N=n)
+    tables = pq.build_tables(torch.from_numpy(W.codewords(w)).to(dev))
+    codes = W.codes_torch(wl, dev)
+    centers = torch.from_numpy(W.codes_at(w, W.init_center_indices(w))).to(dev)
+    a1 = torch.empty(n, dtype=torch.int32, device=dev)
+    a2 = torch.empty(n, dtype=torch.int32, device=dev)
+    ws = torch.empty(pq.workspace_bytes(n, w.M, w.K), dtype=torch.uint8, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    note(f"linear scan over {n} codes x {w.K} centers")
+    ms_scan = timed(lambda: pq.assign(codes, centers, tables, assign=a1, want_dist=False, workspace=ws), 3)
+    note("indexed search over the same codes")
+    ms_index = timed(lambda: pq.assign_indexed(codes, centers, tables, assign=a2, want_dist=False), 1)
+    same = bool(torch.equal(a1, a2))
+    note("Check() on 4096 sampled codes")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed)
+    sample = codes[torch.randperm(n, generator=g)[:4096].to(dev)].contiguous()
+    use_index, c_scan, c_index = pq.check(sample, centers, tables, trials=10)
+    print(json.dumps({
+        "metric": "assignment step: linear scan vs exact index over the centers (Alg. 1, Check)", "value": ms_index / ms_scan,
+        "unit": "x (indexed time / scan time)", "n_gpus": 1, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: first {n} codes, M={w.M}, all K={w.K} initial centers"},
+        "ms_scan": ms_scan, "ms_indexed": ms_index, "same_assignment": same,
+        "check": {"sample": 4096, "trials": 10, "scan_ms": c_scan, "index_ms": c_index, "use_index": use_index}}))
+    return 0
+
+
 def microbench(torch) -> int:
     """The microbenchmarks behind the roofline denominators (paper_1709_03708_amd/csrc/microbench.hip): LDS read
     and write rates, VALU issue rates, the scan's instruction mix with and without a tile switch.  Prints a table
@@ -353,6 +399,10 @@ def main() -> int:
     ap.add_argument("--naive-update", action="store_true",
                     help="time the sparse-voting update (Eq. 7-8) against the naive update (Eq. 6) on the "
                          "configuration's first assignment, as in the paper's per-step runtime table; prints its own line")
+    ap.add_argument("--indexed", action="store_true",
+                    help="time the assignment through the exact index over the centers (Alg. 1's table branch) against "
+                         "the linear scan on a stretch of the configuration's codes, and run Check(); prints its own line")
+    ap.add_argument("--indexed-codes", type=int, default=1 << 20, help="codes of the --indexed comparison")
     ap.add_argument("--microbench", action="store_true",
                     help="run the microbenchmarks behind the roofline denominators (LDS read and write rates, VALU "
                          "issue rates, the scan's instruction mix with and without a tile switch) and print them")
@@ -389,6 +439,8 @@ def main() -> int:
         return encoder_bench(args, W.CONFIGS[args.config], pq, torch, dev)
     if args.naive_update:
         return naive_update_bench(args, W.CONFIGS[args.config], pq, torch, dev)
+    if args.indexed:
+        return indexed_bench(args, W.CONFIGS[args.config], pq, torch, dev)
 
     cfg = args.config
     fallback = None

@@ -129,6 +129,38 @@ pqkm_status pqkm_assign_noalloc(const uint8_t *codes, int64_t N, int32_t M, cons
                                 void *stream);
 
 /*
+ * Assignment step through an exact index over the centers (Sec. 3.1: Alg. 1's BuildTable + FindNN with
+ * the table, the branch the paper takes for very many centers).  Same definition and same result as
+ * pqkm_assign, bit for bit, ties included: the centers are filed in 65536 buckets by their first two
+ * subcodes, and every code walks the buckets in ascending partial distance, stopping a walk once a lower
+ * bound of all that is left (the partial sum continued with the row minima of the remaining subspaces, in
+ * the order of Eq. 3) exceeds the best distance found.  The bounds are exact in fp32 for any table entries
+ * (fp32 addition is monotone); NaN entries only make the walk longer.  How much is pruned depends on the
+ * data: on codes whose nearest center is close the walk is short, on codes far from every center it visits
+ * most buckets and is far slower than the scan.  pqkm_check measures which of the two is faster.
+ *   workspace: at least pqkm_index_workspace_bytes(M, K) bytes; M >= 2.
+ */
+size_t pqkm_index_workspace_bytes(int32_t M, int32_t K);
+pqkm_status pqkm_assign_indexed(const uint8_t *codes, int64_t N, int32_t M, const uint8_t *centers,
+                                int32_t K, const float *tables, int32_t *assign, float *dist,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Check() of Alg. 1 (Sec. 3.1): runs the linear scan and the indexed search on a sample of the codes,
+ * `trials` times each after one warm-up run, and reports the faster (the paper uses 10 trials).
+ *   sample_codes [n_sample][M] u8, in: the sampled codes (the caller draws the sample)
+ *   use_index    host, out: 1 if the indexed search was faster, else 0
+ *   scan_ms, index_ms   host, out, may be NULL: the best time of each, in milliseconds
+ * BLOCKS: it times with HIP events it creates and destroys, and waits for them.
+ *   workspace: at least pqkm_check_workspace_bytes(n_sample, M, K) bytes; M >= 2.
+ */
+size_t pqkm_check_workspace_bytes(int64_t n_sample, int32_t M, int32_t K);
+pqkm_status pqkm_check(const uint8_t *sample_codes, int64_t n_sample, int32_t M, const uint8_t *centers,
+                       int32_t K, const float *tables, int32_t trials, void *workspace,
+                       size_t workspace_bytes, void *stream, int32_t *use_index, float *scan_ms,
+                       float *index_ms);
+
+/*
  * Update step by sparse voting (Eq. 7 then Eq. 8):
  *   hist[k][m][j] = #{ n : assign[n] = k and codes[n][m] = j },  counts[k] = #{ n : assign[n] = k }
  *   centers[k][m] <- argmin_l  sum_{j : hist[k][m][j] > 0} hist[k][m][j] * tables[m][j][l]

@@ -5,8 +5,8 @@ arguments: torch tensors supply device memory, the current torch stream supplies
 stream.  Every step of the path runs in the library's HIP kernels; there is no CPU fallback
 -- a missing library raises at import of the first call.
 """
-from .binding import (NOALLOC_SCRATCH_BYTES, PqkmError, assign, assign_noalloc, build_tables, decode, encode, fit, fit_until, fit_until_workspace_bytes, lib_path, load, profile_read, profile_read_steps, set_option,
+from .binding import (NOALLOC_SCRATCH_BYTES, PqkmError, assign, assign_indexed, assign_noalloc, check, build_tables, decode, encode, fit, fit_until, fit_until_workspace_bytes, lib_path, load, profile_read, profile_read_steps, set_option,
                       status_string, update, update_naive, workspace_bytes)
 
-__all__ = ["NOALLOC_SCRATCH_BYTES", "PqkmError", "assign", "assign_noalloc", "build_tables", "decode", "encode", "fit", "fit_until", "fit_until_workspace_bytes", "lib_path", "load", "profile_read", "profile_read_steps", "set_option",
+__all__ = ["NOALLOC_SCRATCH_BYTES", "PqkmError", "assign", "assign_indexed", "assign_noalloc", "check", "build_tables", "decode", "encode", "fit", "fit_until", "fit_until_workspace_bytes", "lib_path", "load", "profile_read", "profile_read_steps", "set_option",
            "status_string", "update", "update_naive", "workspace_bytes"]

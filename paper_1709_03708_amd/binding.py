@@ -35,6 +35,13 @@ def load():
         lib.pqkm_build_tables.argtypes = [vp, i32, i32, vp, vp]
         lib.pqkm_assign.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.pqkm_assign_noalloc.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp]
+        lib.pqkm_index_workspace_bytes.restype = sz
+        lib.pqkm_index_workspace_bytes.argtypes = [i32, i32]
+        lib.pqkm_assign_indexed.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.pqkm_check_workspace_bytes.restype = sz
+        lib.pqkm_check_workspace_bytes.argtypes = [i64, i32, i32]
+        lib.pqkm_check.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, sz, vp, ctypes.POINTER(i32),
+                                   ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
         lib.pqkm_update.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.pqkm_fit.argtypes = [vp, i64, i32, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.pqkm_fit_until_workspace_bytes.restype = sz
@@ -46,7 +53,7 @@ def load():
         lib.pqkm_set_option.argtypes = [ctypes.c_char_p, i32]
         lib.pqkm_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         lib.pqkm_profile_read_steps.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
-        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_assign_noalloc", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
+        for n in ("pqkm_build_tables", "pqkm_assign", "pqkm_assign_noalloc", "pqkm_assign_indexed", "pqkm_check", "pqkm_update", "pqkm_fit", "pqkm_fit_until", "pqkm_set_option",
                   "pqkm_profile_read", "pqkm_profile_read_steps", "pqkm_encode", "pqkm_decode", "pqkm_update_naive"):
             getattr(lib, n).restype = ctypes.c_int
         _lib = lib
@@ -158,6 +165,48 @@ def assign(codes, centers, tables, assign=None, dist=None, want_dist=True, works
     _check(load().pqkm_assign(_ptr(codes), N, M, _ptr(centers), K, _ptr(tables), _ptr(assign), _ptr(dist),
                               _ptr(workspace), wb, _stream()), "pqkm_assign")
     return assign, dist
+
+
+def assign_indexed(codes, centers, tables, assign=None, dist=None, want_dist=True, workspace=None):
+    """pqkm_assign_indexed (Alg. 1 with the table): same result as assign().  -> (assign, dist or None)."""
+    import torch
+
+    N, M = codes.shape
+    K = centers.shape[0]
+    _need(codes, torch.uint8, (N, M), "codes")
+    _need(centers, torch.uint8, (K, M), "centers")
+    _need(tables, torch.float32, (M, L, L), "tables")
+    if assign is None:
+        assign = torch.empty(N, dtype=torch.int32, device=codes.device)
+    if dist is None and want_dist:
+        dist = torch.empty(N, dtype=torch.float32, device=codes.device)
+    _need(assign, torch.int32, (N,), "assign")
+    _need(dist, torch.float32, (N,), "dist")
+    if workspace is None:
+        workspace = torch.empty(max(int(load().pqkm_index_workspace_bytes(M, K)), 256), dtype=torch.uint8,
+                                device=codes.device)
+    _check(load().pqkm_assign_indexed(_ptr(codes), N, M, _ptr(centers), K, _ptr(tables), _ptr(assign), _ptr(dist),
+                                      _ptr(workspace), workspace.numel(), _stream()), "pqkm_assign_indexed")
+    return assign, dist
+
+
+def check(sample_codes, centers, tables, trials=10, workspace=None):
+    """pqkm_check, Alg. 1's Check(): -> (use_index: bool, scan_ms, index_ms) on the given sample of codes."""
+    import torch
+
+    n, M = sample_codes.shape
+    K = centers.shape[0]
+    _need(sample_codes, torch.uint8, (n, M), "sample_codes")
+    _need(centers, torch.uint8, (K, M), "centers")
+    _need(tables, torch.float32, (M, L, L), "tables")
+    if workspace is None:
+        workspace = torch.empty(max(int(load().pqkm_check_workspace_bytes(n, M, K)), 256), dtype=torch.uint8,
+                                device=sample_codes.device)
+    flag, t_scan, t_index = ctypes.c_int32(0), ctypes.c_float(0), ctypes.c_float(0)
+    _check(load().pqkm_check(_ptr(sample_codes), n, M, _ptr(centers), K, _ptr(tables), int(trials), _ptr(workspace),
+                             workspace.numel(), _stream(), ctypes.byref(flag), ctypes.byref(t_scan),
+                             ctypes.byref(t_index)), "pqkm_check")
+    return bool(flag.value), t_scan.value, t_index.value
 
 
 NOALLOC_SCRATCH_BYTES = 64 * 1024 * 1024

@@ -854,6 +854,45 @@ pqkm_status update_impl(const Options& opt, const Carve& c, const uint8_t* codes
     return launched();
 }
 
+// workspace of the indexed assignment: sorted rows of A^0 and A^1, row minima, bucket counters / starts / cursors, items
+struct IndexCarve { size_t ord_off, rowmin_off, cnt_off, start_off, cursor_off, items_off, total; };
+
+IndexCarve index_carve(int M, int K)
+{
+    IndexCarve c{};
+    size_t off = 0;
+    c.ord_off = off;     off += align256((size_t)2 * L * L);
+    c.rowmin_off = off;  off += align256((size_t)M * L * sizeof(float));
+    c.cnt_off = off;     off += align256((size_t)(INDEX_BUCKETS + 1) * sizeof(uint32_t));
+    c.start_off = off;   off += align256((size_t)(INDEX_BUCKETS + 1) * sizeof(uint32_t));
+    c.cursor_off = off;  off += align256((size_t)(INDEX_BUCKETS + 1) * sizeof(uint32_t));
+    c.items_off = off;   off += align256((size_t)K * sizeof(uint32_t));
+    c.total = off;
+    return c;
+}
+
+// BuildTable + FindNN of Alg. 1 with the table: files the centers, then one lane per code walks the buckets
+pqkm_status assign_indexed_impl(const IndexCarve& c, const uint8_t* codes, int64_t N, int M, const uint8_t* centers, int K,
+                                const float* tables, int32_t* assign, float* dist, char* ws, hipStream_t st)
+{
+    uint8_t* ord = reinterpret_cast<uint8_t*>(ws + c.ord_off);
+    float* rowmin = reinterpret_cast<float*>(ws + c.rowmin_off);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + c.cnt_off);
+    uint32_t* start = reinterpret_cast<uint32_t*>(ws + c.start_off);
+    uint32_t* cursor = reinterpret_cast<uint32_t*>(ws + c.cursor_off);
+    uint32_t* items = reinterpret_cast<uint32_t*>(ws + c.items_off);
+    hipLaunchKernelGGL(index_rows_kernel, dim3(L, (unsigned)M), dim3(256), 0, st, tables, ord, rowmin);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(64), dim3(256), 0, st, cnt, (int64_t)INDEX_BUCKETS);
+    hipLaunchKernelGGL(index_count_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, centers, K, M, cnt);
+    hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, INDEX_BUCKETS, start, cursor);
+    hipLaunchKernelGGL(index_scatter_kernel, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, centers, K, M, start,
+                       cursor, items);
+    if (N > 0)
+        hipLaunchKernelGGL(assign_indexed_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, codes, N, M, centers,
+                           tables, ord, rowmin, start, items, assign, dist);
+    return launched();
+}
+
 template <int DS>
 void launch_encode(const float* vectors, int64_t N, int M, const float* codewords, uint8_t* codes, hipStream_t st)
 {
@@ -961,6 +1000,75 @@ pqkm_status pqkm_assign_noalloc(const uint8_t* codes, int64_t N, int32_t M, cons
     Options opt = options_snapshot();
     opt.profile = 0;                        // the event pairs of the profile option are created on demand
     return assign_impl(opt, c, codes, N, M, centers, K, tables, assign, dist, ws, (hipStream_t)stream);
+}
+
+size_t pqkm_index_workspace_bytes(int32_t M, int32_t K)
+{
+    if (M < 2 || M > 64 || K < 1) return 0;
+    return index_carve(M, K).total;
+}
+
+pqkm_status pqkm_assign_indexed(const uint8_t* codes, int64_t N, int32_t M, const uint8_t* centers, int32_t K,
+                                const float* tables, int32_t* assign, float* dist, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    if (!shape_ok(N, M, K) || M < 2 || N > (int64_t)0x7fffffff * 256) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || (N > 0 && (!codes || !assign))) return PQKM_ERR_NULL;
+    const IndexCarve c = index_carve(M, K);
+    pqkm_status s = check_workspace(workspace, workspace_bytes, c.total);
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    return assign_indexed_impl(c, codes, N, M, centers, K, tables, assign, dist, static_cast<char*>(workspace),
+                               (hipStream_t)stream);
+}
+
+size_t pqkm_check_workspace_bytes(int64_t n_sample, int32_t M, int32_t K)
+{
+    if (!shape_ok(n_sample, M, K) || M < 2) return 0;
+    const size_t a = carve(n_sample, M, K).total, b = index_carve(M, K).total;
+    return (a > b ? a : b) + align256((size_t)n_sample * sizeof(int32_t));
+}
+
+pqkm_status pqkm_check(const uint8_t* sample_codes, int64_t n_sample, int32_t M, const uint8_t* centers, int32_t K,
+                       const float* tables, int32_t trials, void* workspace, size_t workspace_bytes, void* stream,
+                       int32_t* use_index, float* scan_ms, float* index_ms)
+{
+    if (!shape_ok(n_sample, M, K) || M < 2 || n_sample < 1 || trials < 1) return PQKM_ERR_SHAPE;
+    if (!centers || !tables || !sample_codes || !use_index) return PQKM_ERR_NULL;
+    const Carve ca = carve(n_sample, M, K);
+    const IndexCarve ci = index_carve(M, K);
+    const size_t shared = ca.total > ci.total ? ca.total : ci.total;
+    pqkm_status s = check_workspace(workspace, workspace_bytes, shared + align256((size_t)n_sample * sizeof(int32_t)));
+    if (s != PQKM_OK) return s;
+    if ((s = check_device()) != PQKM_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    int32_t* out = reinterpret_cast<int32_t*>(ws + shared);
+    Options opt = options_snapshot();
+    opt.profile = 0;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return PQKM_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return PQKM_ERR_DEVICE; }
+    float best_ms[2] = {0.f, 0.f};
+    for (int which = 0; which < 2 && s == PQKM_OK; ++which) {
+        for (int t = 0; t <= trials && s == PQKM_OK; ++t) {          // trial 0 is a warm-up and is not counted
+            if (hipEventRecord(e0, st) != hipSuccess) { s = PQKM_ERR_DEVICE; break; }
+            s = which == 0 ? assign_impl(opt, ca, sample_codes, n_sample, M, centers, K, tables, out, nullptr, ws, st)
+                           : assign_indexed_impl(ci, sample_codes, n_sample, M, centers, K, tables, out, nullptr, ws, st);
+            if (s != PQKM_OK) break;
+            float ms = 0.f;
+            if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { s = PQKM_ERR_DEVICE; break; }
+            if (t == 1 || (t > 1 && ms < best_ms[which])) best_ms[which] = ms;
+        }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (s != PQKM_OK) return s;
+    if (scan_ms) *scan_ms = best_ms[0];
+    if (index_ms) *index_ms = best_ms[1];
+    *use_index = best_ms[1] < best_ms[0] ? 1 : 0;
+    return PQKM_OK;
 }
 
 pqkm_status pqkm_update(const uint8_t* codes, int64_t N, int32_t M, const int32_t* assign, int32_t K,

@@ -2644,6 +2644,123 @@ __global__ __launch_bounds__(VOTE_THREADS) void vote_kernel(uint32_t* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
+// Exact index over the centers (Sec. 3.1, the table-based FindNN of Alg. 1).
+//
+// The paper's table is a hash table over the center codes that is probed with candidate codes in
+// ascending distance until a stored one is met.  Here the centers are filed in 65536 buckets by their
+// first two subcodes (c0, c1); a code (x0, x1, ...) walks the buckets in ascending A^0[x0][c0] and, inside,
+// ascending A^1[x1][c1] -- two sorted rows -- and stops a walk as soon as a lower bound of everything
+// that is left exceeds the best distance found.  The bound of a bucket is its partial sum continued with
+// the smallest entry of the code's row in every remaining subspace, added in the order of Eq. 3: fp32
+// addition is monotone in both operands, so the bound is never above the fp32 distance of any center of
+// the bucket, the pruning is exact, and a NaN bound (comparisons false) prunes nothing.  Every visited
+// center gets its full distance in the sequential order of Eq. 3; ties go to the lowest center index by
+// comparing (distance, index), so the result is that of the linear scan bit for bit.
+// One lane per code: the walks diverge, and every probe is a trip to memory rather than to the LDS.
+// ---------------------------------------------------------------------------------------------
+constexpr int INDEX_BUCKETS = 65536;
+
+// grid (256, M), block 256: row x of A^m.  rowmin[m][x] = its smallest non-NaN entry (+inf if there is none);
+// for m < 2 also ord[m][x][i] = the columns in ascending order of their entries (NaN last, ties by column)
+__global__ __launch_bounds__(256) void index_rows_kernel(const float* __restrict__ tables, uint8_t* __restrict__ ord,
+                                                         float* __restrict__ rowmin)
+{
+    __shared__ float row[L];
+    __shared__ float red[4];
+    const int x = blockIdx.x, m = blockIdx.y, c = threadIdx.x;
+    const float v = tables[((size_t)m * L + x) * L + c];
+    row[c] = v;
+    float mn = (v != v) ? INFINITY : v;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mn = __builtin_fminf(mn, __shfl_xor(mn, d));
+    if ((c & 63) == 0) red[c >> 6] = mn;
+    __syncthreads();
+    if (c == 0) rowmin[m * L + x] = __builtin_fminf(__builtin_fminf(red[0], red[1]), __builtin_fminf(red[2], red[3]));
+    if (m >= 2) return;
+    const bool vnan = v != v;
+    int rank = 0;
+    for (int o = 0; o < L; ++o) {
+        const float u = row[o];
+        const bool unan = u != u;
+        const bool before = (!unan && (vnan || u < v)) || ((u == v || (unan && vnan)) && o < c);
+        rank += before ? 1 : 0;
+    }
+    ord[((size_t)m * L + x) * L + rank] = (uint8_t)c;
+}
+
+__global__ __launch_bounds__(256) void index_count_kernel(const uint8_t* __restrict__ centers, int K, int M,
+                                                          uint32_t* __restrict__ cnt)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    atomicAdd(&cnt[(uint32_t)centers[(size_t)k * M] * 256u + centers[(size_t)k * M + 1]], 1u);
+}
+
+__global__ __launch_bounds__(256) void index_scatter_kernel(const uint8_t* __restrict__ centers, int K, int M,
+                                                            const uint32_t* __restrict__ start,
+                                                            uint32_t* __restrict__ cursor, uint32_t* __restrict__ items)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    const uint32_t b = (uint32_t)centers[(size_t)k * M] * 256u + centers[(size_t)k * M + 1];
+    items[start[b] + atomicAdd(&cursor[b], 1u)] = (uint32_t)k;
+}
+
+__global__ __launch_bounds__(256) void assign_indexed_kernel(const uint8_t* __restrict__ codes, int64_t N, int M,
+                                                             const uint8_t* __restrict__ centers,
+                                                             const float* __restrict__ tables,
+                                                             const uint8_t* __restrict__ ord,
+                                                             const float* __restrict__ rowmin,
+                                                             const uint32_t* __restrict__ start,
+                                                             const uint32_t* __restrict__ items,
+                                                             int32_t* __restrict__ assign, float* __restrict__ dist)
+{
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const uint8_t* x = codes + n * M;
+    const int x0 = x[0], x1 = x[1];
+    const float* A0 = tables + (size_t)x0 * L;
+    const float* A1 = tables + ((size_t)L + x1) * L;
+    const uint8_t* o0 = ord + (size_t)x0 * L;
+    const uint8_t* o1 = ord + ((size_t)L + x1) * L;
+    // what the subspaces 2 .. M-1 add at least, continued in the order of Eq. 3
+    auto bound = [&](float p) -> float {
+        for (int m = 2; m < M; ++m) p = p + rowmin[m * L + x[m]];
+        return p;
+    };
+    float best = INFINITY;
+    int bk = IDX_NONE;
+    const float d1min = A1[o1[0]];
+    for (int i = 0; i < L; ++i) {
+        const int c0 = o0[i];
+        const float d0 = A0[c0];
+        if (bound(d0 + d1min) > best) break;                 // every later c0 has a larger bound
+        for (int jj = 0; jj < L; ++jj) {
+            const int c1 = o1[jj];
+            const float p = d0 + A1[c1];
+            if (bound(p) > best) break;                      // so has every later c1 under this c0
+            const uint32_t b = (uint32_t)c0 * 256u + (uint32_t)c1;
+            const uint32_t e1 = start[b + 1];
+            for (uint32_t e = start[b]; e < e1; ++e) {
+                const int k = (int)items[e];
+                const uint8_t* mu = centers + (size_t)k * M;
+                float sd = p;
+                for (int m = 2; m < M; ++m) {
+                    const float a = tables[((size_t)m * L + x[m]) * L + mu[m]];
+                    sd = sd + a;
+                }
+                if (sd < best || (sd == best && bk != IDX_NONE && k < bk)) {
+                    best = sd;
+                    bk = k;
+                }
+            }
+        }
+    }
+    assign[n] = (bk == IDX_NONE) ? 0 : bk;
+    if (dist) dist[n] = best;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Per-iteration statistics of the convergence-checked loop (Alg. 1 with a stop condition).
 // All reductions run in a fixed order (per-lane strided sums, xor-shuffle tree, per-block partials
 // summed by one wave), so the fp64 objective is reproducible from run to run.

@@ -274,6 +274,83 @@ def test_assign_degenerate_inputs(env):
     np.testing.assert_array_equal(a.cpu().numpy(), env["oracle"].assign(codes, centers, tables)[0])
 
 
+# ------------------------------------------------------------------------------------ indexed assignment, Check()
+def _check_assign_indexed(env, codes, centers, tables):
+    pq, oracle = env["pq"], env["oracle"]
+    a, d = pq.assign_indexed(_dev(env, codes), _dev(env, centers), _dev(env, tables))
+    _sync(env)
+    ra, rd = oracle.assign(codes, centers, tables)
+    np.testing.assert_array_equal(a.cpu().numpy(), ra)
+    np.testing.assert_array_equal(d.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+
+
+@pytest.mark.parametrize("cfg,over", [(1, {}), (2, dict(N=30_001, K=1000)), (5, dict(N=20_001, K=100_000)),
+                                      (3, dict(N=6_001, K=700, T=900)), (4, dict(N=1_001, K=90, T=50)),
+                                      (1, dict(N=3_000, K=1)), (2, dict(N=2_000, K=300, M=2, D=64))])
+def test_assign_indexed_matches_oracle(env, cfg, over):
+    """Alg. 1's FindNN with the table: the bucket index over the centers must give the linear scan's result bit
+    for bit (the oracle is the same pqko_assign), from toy sizes to the billion-scale configuration's 1e5 centers
+    (all of them, against a stretch of its codes), for 2 to 32 subspaces."""
+    W = env["W"]
+    w = workload(cfg, **over)
+    n_gen = max(w.N, 1)
+    codes = W.codes_numpy(dataclasses.replace(w, N=n_gen)) if w.N <= 5_000_000 else None
+    centers = W.codes_at(w, W.init_center_indices(w)) if w.K <= w.N else None
+    if centers is None:
+        # more centers than codes in this stretch: the centers are the configuration's own (drawn from all its codes)
+        full = workload(cfg)
+        centers = W.codes_at(full, W.init_center_indices(full))[: w.K]
+    tables = env["oracle"].build_tables(W.codewords(w))
+    _check_assign_indexed(env, codes, centers, tables)
+    progress(f"indexed assignment cfg {cfg} {over}: bit-exact")
+
+
+@pytest.mark.parametrize("M", [2, 4, 8])
+def test_assign_indexed_ties_and_non_finite_tables(env, M):
+    """Hamming tables (massive ties: the lowest center index must win although the walk meets the centers in
+    bucket order), duplicated centers, and tables with NaN and infinite entries (bounds that are NaN prune
+    nothing; +inf sums are never selected)."""
+    rng = np.random.default_rng(70 + M)
+    ham = np.ones((M, 256, 256), np.float32)
+    for m in range(M):
+        np.fill_diagonal(ham[m], 0)
+    codes = rng.integers(0, 3, size=(3000, M), dtype=np.uint8)
+    centers = rng.integers(0, 3, size=(200, M), dtype=np.uint8)
+    _check_assign_indexed(env, codes, centers, ham)
+    _check_assign_indexed(env, codes, codes[:1500].copy(), ham)
+    codes = rng.integers(0, 256, size=(2000, M), dtype=np.uint8)
+    centers = rng.integers(0, 256, size=(400, M), dtype=np.uint8)
+    _check_assign_indexed(env, codes, centers, rand_tables(rng, M))            # non-symmetric
+    _check_assign_indexed(env, codes, centers, rand_tables(rng, M, integer=True))
+    for kind in ("mixed", "all_inf", "all_nan"):
+        t = rand_tables(rng, M)
+        flat = t.reshape(-1)
+        if kind == "mixed":
+            idx = rng.choice(flat.size, flat.size // 20, replace=False)
+            flat[idx[0::3]] = np.nan
+            flat[idx[1::3]] = np.inf
+            flat[idx[2::3]] = -np.inf
+        else:
+            flat[:] = np.inf if kind == "all_inf" else np.nan
+        _check_assign_indexed(env, codes[:500], centers, t)
+
+
+def test_check_times_both_and_names_the_faster(env):
+    """Check() of Alg. 1: both searches are run on the sample; the flag names the faster one."""
+    pq, W, torch = env["pq"], env["W"], env["torch"]
+    w = workload(2, N=20_000, K=2_000)
+    codes = W.codes_numpy(w)
+    centers = codes[W.init_center_indices(w)].copy()
+    tables = env["oracle"].build_tables(W.codewords(w))
+    use_index, t_scan, t_index = pq.check(_dev(env, codes[:4096]), _dev(env, centers), _dev(env, tables), trials=3)
+    assert t_scan > 0 and t_index > 0
+    assert use_index == (t_index < t_scan)
+    # N = 0 is legal for the indexed assignment
+    a, _ = pq.assign_indexed(torch.empty((0, 4), dtype=torch.uint8, device=env["dev"]), _dev(env, centers), _dev(env, tables))
+    assert a.numel() == 0
+    progress(f"Check(): scan {t_scan:.3f} ms, index {t_index:.3f} ms on 4096 codes x 2000 centers -> use_index={use_index}")
+
+
 # ------------------------------------------------------------------------------------ update
 @pytest.mark.parametrize("hist_kernel", [0, 1, 2, 3])
 @pytest.mark.parametrize("M,K,N", [(4, 37, 3001), (8, 100, 5000), (3, 11, 700), (32, 9, 2000), (4, 70, 300_000),
