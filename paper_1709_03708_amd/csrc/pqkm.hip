@@ -86,7 +86,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
         gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, pool_off, bseg_off, skew_off,
-        total;
+        rank_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -171,6 +171,8 @@ Carve carve(int64_t N, int M, int K)
         off += align256((size_t)N * sizeof(uint32_t));
         c.seg_off = off;
         off += 3 * align256(((size_t)K + 1) * sizeof(uint32_t));
+        c.rank_off = off;                    // every code's rank inside its cluster, left by the scan (pqkm_fit)
+        off += align256((size_t)N * sizeof(uint32_t));
     }
     c.gc8_off = c.plan8_off = off;
     if (M == 8) {
@@ -274,12 +276,13 @@ void launch_scan4s(const uint8_t* codes, int64_t N, const float4* img, int ntile
 
 template <int R, int THREADS, int DEPTH, bool BUCKET = false>
 void launch_scan4p(const uint8_t* codes, int64_t N, const uint2* gco, const float4* img, const float4* rows,
-                   int ntiles, int32_t* assign, float* dist, hipStream_t st, BucketOut bo = BucketOut{})
+                   int ntiles, int32_t* assign, float* dist, hipStream_t st, BucketOut bo = BucketOut{},
+                   RankOut ro = RankOut{})
 {
     constexpr int C = (THREADS / 4) * R;
     int64_t nwg = (N + C - 1) / C;
     hipLaunchKernelGGL((assign_scan4p_kernel<R, THREADS, DEPTH, BUCKET>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes,
-                       N, gco, img, rows, ntiles, assign, dist, bo);
+                       N, gco, img, rows, ntiles, assign, dist, bo, ro);
 }
 
 template <int M, int R, int THREADS, int DEPTH = 1>
@@ -307,12 +310,12 @@ inline int variant_layout(int M, int variant)
 
 template <int R, int THREADS, int DEPTH>
 void launch_scan8p(const uint8_t* codes, int64_t N, const uint4* gc8, const float4* img, int ntiles, int32_t* assign,
-                   float* dist, hipStream_t st)
+                   float* dist, hipStream_t st, RankOut ro = RankOut{})
 {
     constexpr int C = (THREADS / 4) * R;
     int64_t nwg = (N + C - 1) / C;
     hipLaunchKernelGGL((assign_scan8p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
-                       gc8, img, ntiles, assign, dist);
+                       gc8, img, ntiles, assign, dist, ro);
 }
 
 template <int M>
@@ -340,7 +343,7 @@ inline int sw_codes_per_slot(int variant, int64_t n)
 
 template <int M>
 pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_t* S, const float4* img, int ntiles16,
-                           int32_t* assign, float* dist, hipStream_t st)
+                           int32_t* assign, float* dist, hipStream_t st, RankOut ro = RankOut{})
 {
     const int R = sw_codes_per_slot(variant, N);
     const int64_t C = 256 * (int64_t)R;
@@ -351,11 +354,11 @@ pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_
     switch (R) {
         case 8:
             hipLaunchKernelGGL((assign_scan_sw_kernel<M, 8, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
-                               n_alloc, img, ntiles16, assign, dist);
+                               n_alloc, img, ntiles16, assign, dist, ro);
             break;
         default:
             hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
-                               n_alloc, img, ntiles16, assign, dist);
+                               n_alloc, img, ntiles16, assign, dist, ro);
             break;
     }
     return launched();
@@ -385,14 +388,14 @@ int scan4p_codes_per_slot(int64_t n_alloc)
 // only); *nwg_out receives the number of scan workgroups = the row length of the segment table
 void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
                          int ntiles, int32_t* assign, float* dist, hipStream_t st, const BucketOut* bo = nullptr,
-                         int* nwg_out = nullptr)
+                         int* nwg_out = nullptr, RankOut ro = RankOut{})
 {
     int R = 0;
     switch (variant) {
         case 70: R = scan4p_codes_per_slot(n_alloc); break;
         case 71: R = 28; break;
         case 72: R = 31; break;
-        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); return;
+        case 73: launch_scan4p<16, 1024, 1>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); return;
         case 74: R = 24; break;
         case 75: R = 20; break;
         case 76: R = 16; break;
@@ -411,12 +414,12 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
         return;
     }
     switch (R) {
-        case 16: launch_scan4p<16, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 20: launch_scan4p<20, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 24: launch_scan4p<24, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 28: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        case 31: launch_scan4p<31, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
-        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st); break;
+        case 16: launch_scan4p<16, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
+        case 20: launch_scan4p<20, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
+        case 24: launch_scan4p<24, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
+        case 28: launch_scan4p<28, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
+        case 31: launch_scan4p<31, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
+        default: launch_scan4p<32, 512, 3>(nullptr, n_alloc, gco, img, rows, ntiles, assign, dist, st, BucketOut{}, ro); break;
     }
 }
 
@@ -438,14 +441,14 @@ int scan8p_codes_per_slot(int64_t n_alloc)
 }
 
 void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
-                          float* dist, hipStream_t st)
+                          float* dist, hipStream_t st, RankOut ro = RankOut{})
 {
     int R = 0;
     switch (variant) {
         case 70: R = scan8p_codes_per_slot(n_alloc); break;
-        case 71: launch_scan8p<12, 1024, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); return;
-        case 72: launch_scan8p<16, 512, 8>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); return;
-        case 73: launch_scan8p<24, 512, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); return;
+        case 71: launch_scan8p<12, 1024, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
+        case 72: launch_scan8p<16, 512, 8>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
+        case 73: launch_scan8p<24, 512, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
         case 74: R = 25; break;
         case 75: R = 22; break;
         case 76: R = 20; break;
@@ -454,12 +457,12 @@ void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const 
         default: R = 24; break;
     }
     switch (R) {
-        case 16: launch_scan8p<16, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
-        case 18: launch_scan8p<18, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
-        case 20: launch_scan8p<20, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
-        case 22: launch_scan8p<22, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
-        case 25: launch_scan8p<25, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
-        default: launch_scan8p<24, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st); break;
+        case 16: launch_scan8p<16, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        case 18: launch_scan8p<18, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        case 20: launch_scan8p<20, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        case 22: launch_scan8p<22, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        case 25: launch_scan8p<25, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        default: launch_scan8p<24, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
     }
 }
 
@@ -610,6 +613,8 @@ inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) &&
 struct BucketLink {
     bool wanted = false, produced = false;
     int KT = 0, ngroups = 0, nwg = 0;
+    // the other hand-over (sorted-path sizes): every code's rank inside its cluster, counted by the scan's epilogue
+    bool rank_wanted = false, ranked = false;
 };
 
 template <int M>
@@ -649,8 +654,19 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
     uint4* gc8 = reinterpret_cast<uint4*>(ws + c.gc8_off);
     GroupPlan8* plan8 = reinterpret_cast<GroupPlan8*>(ws + c.plan8_off);
+    // ranks for the sorted-path histogram: from the scans that finish their codes one per lane (the regrouped scans
+    // and the sliding-window scan), unless this iteration already hands records over by cluster group
+    RankOut ro{};
+    if (link && link->rank_wanted && (grouped || sliding) && !(M == 4 && link->wanted && variant == 70 && N <= per_launch)) {
+        ro.count = reinterpret_cast<uint32_t*>(ws + c.seg_off);
+        ro.rank = reinterpret_cast<uint32_t*>(ws + c.rank_off);
+        unsigned zb = (unsigned)((K + 255) / 256 < 1024 ? (K + 255) / 256 : 1024);
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, ro.count, (int64_t)K);
+        link->ranked = true;
+    }
     for (int64_t n0 = 0; n0 < N; n0 += per_launch) {
         int64_t cnt = N - n0 < per_launch ? N - n0 : per_launch;
+        const RankOut rl{ro.count, ro.count ? ro.rank + n0 : nullptr};
         // the regrouped copy survives between calls only when one launch covers all codes
         if (grouped && !(reuse_groups && N <= per_launch)) {
             const pqkm_status rs = (M == 8) ? regroup_codes8(codes + n0 * M, cnt, gc8, plan8, st)
@@ -663,12 +679,12 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             if constexpr (M == 16 || M == 32) {
                 if (launch_scan_sw<M>(variant, codes + n0 * M, cnt, reinterpret_cast<uint32_t*>(ws + c.skew_off),
                                       reinterpret_cast<const float4*>(img), (int)ntiles, assign + n0,
-                                      dist ? dist + n0 : nullptr, st) != PQKM_OK)
+                                      dist ? dist + n0 : nullptr, st, rl) != PQKM_OK)
                     return PQKM_ERR_DEVICE;
             }
         } else if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
-                                 assign + n0, dist ? dist + n0 : nullptr, st);
+                                 assign + n0, dist ? dist + n0 : nullptr, st, rl);
         else if (grouped && M == 4 && link && link->wanted && variant == 70 && N <= per_launch &&
                  c.bseg_off != c.pool_off) {
             BucketOut bo{reinterpret_cast<uint2*>(ws + c.pool_off), reinterpret_cast<uint2*>(ws + c.bseg_off), link->KT,
@@ -678,7 +694,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             link->produced = true;
         } else if (grouped)
             launch_scan_grouped(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows,
-                                (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st);
+                                (int)ntiles, assign + n0, dist ? dist + n0 : nullptr, st, nullptr, nullptr, rl);
         else
             launch_scan_M<M>(variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                              assign + n0, dist ? dist + n0 : nullptr, st);
@@ -703,9 +719,9 @@ pqkm_status assign_core(const Options& opt, const Carve& c, const uint8_t* codes
     char* wsc = static_cast<char*>(ws);
     switch (M) {
         case 4: return assign_tiled<4>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st, link);
-        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st);
-        case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
-        default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st);
+        case 8: return assign_tiled<8>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, reuse_groups, st, link);
+        case 16: return assign_tiled<16>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st, link);
+        default: return assign_tiled<32>(codes, N, centers, K, tables, assign, dist, img, opt, c, wsc, false, st, link);
     }
 }
 
@@ -724,21 +740,30 @@ pqkm_status assign_impl(const Options& opt, const Carve& c, const uint8_t* codes
 
 // counting sort of the code indices by cluster into the workspace: start[0..K] and sidx[0..#valid)
 void sort_by_cluster(const int32_t* assign, int64_t N, int K, const Carve& c, char* ws, uint32_t** start_out,
-                     uint32_t** sidx_out, hipStream_t st)
+                     uint32_t** sidx_out, hipStream_t st, bool ranked = false)
 {
     const size_t seg_stride = align256(((size_t)K + 1) * sizeof(uint32_t));
     uint32_t* sidx = reinterpret_cast<uint32_t*>(ws + c.sidx_off);
     uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + c.seg_off);
     uint32_t* start = reinterpret_cast<uint32_t*>(ws + c.seg_off + seg_stride);
     uint32_t* cursor = reinterpret_cast<uint32_t*>(ws + c.seg_off + 2 * seg_stride);
+    unsigned sb = (unsigned)((N + 1023) / 1024 < 8192 ? (N + 1023) / 1024 : 8192);
+    if (sb < 1) sb = 1;
+    if (ranked) {
+        // the scan of this iteration counted the clusters and left every code's rank: prefix, then place
+        const uint32_t* rank = reinterpret_cast<const uint32_t*>(ws + c.rank_off);
+        hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, K, start, cursor);
+        hipLaunchKernelGGL(seg_place_kernel, dim3(sb), dim3(256), 0, st, assign, rank, N, K, start, sidx);
+        *start_out = start;
+        *sidx_out = sidx;
+        return;
+    }
     unsigned zb = (unsigned)((K + 255) / 256 < 1024 ? (K + 255) / 256 : 1024);
     hipLaunchKernelGGL(zero_u32_kernel, dim3(zb), dim3(256), 0, st, cnt, (int64_t)K);
     unsigned cb = (unsigned)((N + 4095) / 4096 < 1024 ? (N + 4095) / 4096 : 1024);
     if (cb < 1) cb = 1;
     hipLaunchKernelGGL(seg_count_kernel, dim3(cb), dim3(1024), 0, st, assign, N, K, cnt);
     hipLaunchKernelGGL(seg_prefix_kernel, dim3(1), dim3(1024), 0, st, cnt, K, start, cursor);
-    unsigned sb = (unsigned)((N + 1023) / 1024 < 8192 ? (N + 1023) / 1024 : 8192);
-    if (sb < 1) sb = 1;
     hipLaunchKernelGGL(seg_scatter_kernel, dim3(sb), dim3(256), 0, st, assign, N, K, start, cursor, sidx);
     *start_out = start;
     *sidx_out = sidx;
@@ -755,9 +780,12 @@ bool owner_histogram(const HistPlan& hp, int force)
 BucketLink bucket_request(const Options& opt, int64_t N, int M, int K)
 {
     BucketLink l;
-    if (M != 4 || N < 1) return l;
+    if (N < 1) return l;
     const HistPlan hp = hist_plan(N, M, K);
     const int force = opt.hist_kernel;
+    // sorted-path sizes: the scan counts the clusters and leaves every code's rank
+    if (force == 0 && !owner_histogram(hp, force) && N <= (int64_t)0xffffffff && M <= 128) l.rank_wanted = true;
+    if (M != 4) return l;
     if (force != 0 || !owner_histogram(hp, force)) return l;     // a forced histogram kernel is used as named
     l.wanted = true;
     l.KT = hp.KT;
@@ -828,7 +856,7 @@ pqkm_status update_impl(const Options& opt, const Carve& c, const uint8_t* codes
     } else if (force != 1 && N <= (int64_t)0xffffffff && N > 0 && M <= 128) {
         // sorted path: counting sort of the code indices by cluster, then LDS histograms per stretch of clusters
         uint32_t *start, *sidx;
-        sort_by_cluster(assign, N, K, c, static_cast<char*>(ws), &start, &sidx, st);
+        sort_by_cluster(assign, N, K, c, static_cast<char*>(ws), &start, &sidx, st, link && link->ranked);
         int KT = (HIST_LDS_WORDS / L) / M;
         if (KT > 128) KT = 128;
         hipLaunchKernelGGL(seg_hist_kernel, dim3((unsigned)((K + KT - 1) / KT)), dim3(1024), 0, st, codes, M, start, sidx,

@@ -891,6 +891,16 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
 // What the scan leaves for the histogram pass when BUCKET is set: workgroup w files its codes by cluster group
 // (KT consecutive clusters) into its own stretch [w*C, (w+1)*C) of `pool` as (code, center) records, the groups
 // one after the other, and notes (first record, number of records) of group g in seg[g * gridDim.x + w].
+// What a scan leaves for the sorted-path histogram when `count` is set: count[k] is incremented for every code
+// assigned to center k (it must be zero before the first scan launch of the assignment step) and rank[n] receives
+// the value the increment returned, the code's place among the members of its cluster.  With the exclusive prefix
+// of the counts that is the code's position in the order by cluster: no counting pass over the assignments and no
+// atomics in the scatter.
+struct RankOut {
+    uint32_t* count = nullptr;
+    uint32_t* rank = nullptr;
+};
+
 struct BucketOut {
     uint2* pool;
     uint2* seg;
@@ -904,7 +914,8 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
                                                                 const float4* __restrict__ img,
                                                                 const float4* __restrict__ rows, int ntiles,
                                                                 int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist, BucketOut bo)
+                                                                float* __restrict__ dist, BucketOut bo,
+                                                                RankOut ro = RankOut{})
 {
     constexpr int LPS = 4, TK = 32;
     constexpr int SLOTS = THREADS / LPS;
@@ -1142,8 +1153,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
         for (int e = 0; e < EB; ++e) {
             if (og[e] != ORIGIN_NONE) {
                 const int64_t dst = gco ? (int64_t)og[e] : base + (i0 + e) * THREADS + tid;
-                assign[dst] = (bi[e] == IDX_NONE) ? 0 : bi[e];
+                const int kw = (bi[e] == IDX_NONE) ? 0 : bi[e];
+                assign[dst] = kw;
                 if (dist) dist[dst] = smin[e];
+                if (ro.count) ro.rank[dst] = atomicAdd(&ro.count[kw], 1u);
             }
             if (BUCKET && i0 + e < CPL) {
                 // the code's 32-byte slot of records has been read (by this lane only): it now keeps the code, its
@@ -1439,7 +1452,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
                                                                 const uint4* __restrict__ gc8,
                                                                 const float4* __restrict__ img, int ntiles,
                                                                 int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist)
+                                                                float* __restrict__ dist, RankOut ro = RankOut{})
 {
     constexpr int LPS = 4, TK = 16, M = 8;
     constexpr int SLOTS = THREADS / LPS;
@@ -1606,8 +1619,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
         }
         if (og != ORIGIN_NONE) {
             const int64_t dst = gc8 ? (int64_t)og : base + j;
-            assign[dst] = (bi == IDX_NONE) ? 0 : bi;
+            const int kw = (bi == IDX_NONE) ? 0 : bi;
+            assign[dst] = kw;
             if (dist) dist[dst] = sm;
+            if (ro.count) ro.rank[dst] = atomicAdd(&ro.count[kw], 1u);
         }
     }
 }
@@ -1846,7 +1861,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
                                                                  const uint32_t* __restrict__ S, int64_t n_alloc,
                                                                  const float4* __restrict__ img, int ntiles,
                                                                  int32_t* __restrict__ assign,
-                                                                 float* __restrict__ dist)
+                                                                 float* __restrict__ dist, RankOut ro = RankOut{})
 {
     constexpr int TK = 16, LPS = 2, NPH = M / 4 + 1;
     constexpr int SLOTS = THREADS / LPS;
@@ -2054,8 +2069,10 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
             if (ob < bv || (ob == bv && oi < bi)) { bv = ob; bi = oi; }
         }
         if (q == 0 && n < N) {
-            assign[n] = (bi == IDX_NONE) ? 0 : bi;
+            const int kw = (bi == IDX_NONE) ? 0 : bi;
+            assign[n] = kw;
             if (dist) dist[n] = bv;
+            if (ro.count) ro.rank[n] = atomicAdd(&ro.count[kw], 1u);
         }
     }
 }
@@ -2166,6 +2183,17 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(const int32_t* __restr
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
         const int k = assign[i];
         if ((unsigned)k < (unsigned)K) sidx[start[k] + atomicAdd(&cursor[k], 1u)] = (uint32_t)i;
+    }
+}
+
+// the scatter when the scan has left every code's rank inside its cluster: no atomics, one pass
+__global__ __launch_bounds__(256) void seg_place_kernel(const int32_t* __restrict__ assign,
+                                                        const uint32_t* __restrict__ rank, int64_t N, int K,
+                                                        const uint32_t* __restrict__ start, uint32_t* __restrict__ sidx)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < N; i += (int64_t)gridDim.x * 256) {
+        const int k = assign[i];
+        if ((unsigned)k < (unsigned)K) sidx[start[k] + rank[i]] = (uint32_t)i;
     }
 }
 

@@ -50,8 +50,9 @@ def test_workspace_bytes_is_host_arithmetic(lib):
     b = pq.workspace_bytes(10**6, 4, 1000)
     assert b >= 32 * 131072 + 1000 * 4 * 256 * 4 + 1000 * 4
     assert b % 256 == 0
-    # config 5: 4 bytes per code of sorted indices, two copies of the tile images, one launch of regrouped codes
-    assert 4 * 10**9 <= pq.workspace_bytes(10**9, 4, 10**5) < 6 * 2**30
+    # config 5: 4 bytes per code of sorted indices and 4 of ranks inside the clusters, two copies of the tile
+    # images, one launch of regrouped codes
+    assert 8 * 10**9 <= pq.workspace_bytes(10**9, 4, 10**5) < 10 * 2**30
     assert pq.fit_until_workspace_bytes(10**6, 4, 1000) >= b + 8 * 10**6
     # a generic M needs no tile images
     assert pq.workspace_bytes(100, 5, 10) < 131072

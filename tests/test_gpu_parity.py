@@ -665,6 +665,33 @@ def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     progress(f"fused fit N={N} K={K} {kind}: bit-exact, {int((rcnt == 0).sum())} empty clusters")
 
 
+@pytest.mark.parametrize("M,N,K", [(4, 600_007, 20_000), (8, 4_300_003, 10_000), (32, 300_007, 3_000), (16, 420_001, 5_000),
+                                   (4, 70_001, 20_000)])
+def test_fit_hands_ranks_to_the_sorted_histogram(env, M, N, K):
+    """pqkm_fit at sizes where the histogram sorts the code indices by cluster (more than 255 cluster groups): the
+    regrouped scans (4- and 8-byte codes) and the sliding-window scan (16, 32 bytes) count the clusters in their
+    epilogue and leave every code's rank, so the update needs no counting pass and no atomics in its scatter.  The
+    last case takes a scan without that hand-over through the same call.  Two iterations against the oracle's loop:
+    centers, assignments, histograms, counts."""
+    pq, oracle, W, torch = env["pq"], env["oracle"], env["W"], env["torch"]
+    w = workload(2 if M == 4 else 3, N=N, K=K, M=M, D=16 * M)
+    codes = W.codes_numpy(w)
+    cent0 = codes[W.init_center_indices(w)].copy()
+    tables = oracle.build_tables(W.codewords(w))
+    hist = torch.empty((K, M, 256), dtype=torch.int32, device=env["dev"])
+    counts = torch.empty((K,), dtype=torch.int32, device=env["dev"])
+    d_cent = _dev(env, cent0)
+    progress(f"fit with rank hand-over M={M} N={N} K={K}: GPU")
+    _, fa = pq.fit(_dev(env, codes), _dev(env, tables), d_cent, 2, hist=hist, counts=counts)
+    _sync(env)
+    progress(f"fit with rank hand-over M={M} N={N} K={K}: oracle")
+    rc, ra, rh, rcnt = oracle.fit(codes, tables, cent0, 2)
+    np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+    np.testing.assert_array_equal(u32(hist), rh)
+    np.testing.assert_array_equal(u32(counts), rcnt)
+    np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
 def test_config1_tiny_all_iterations(env):
     empties = _run_config_full(env, 1, workload(1).iters)
     assert empties > 0          # duplicate initial centers guarantee empty clusters here
