@@ -91,7 +91,7 @@ struct Carve {
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
 constexpr int64_t GROUP_CHUNK_MAX = (int64_t)1 << 26;
-inline int64_t group_alloc(int64_t n) { return (n + 14) & ~(int64_t)7; }   // regrouped positions for n codes
+inline int64_t group_alloc(int64_t n) { return (n + 30) & ~(int64_t)15; }  // regrouped positions for n codes
 constexpr int SW_C_MAX = 256 * 16;          // most codes a workgroup of the sliding-window scan takes
 inline int64_t sw_alloc(int64_t n) { return ((n + SW_C_MAX - 1) / SW_C_MAX + 1) * SW_C_MAX; }   // whole workgroups of any shape
 
@@ -301,7 +301,7 @@ void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int nt
 inline int variant_layout(int M, int variant)
 {
     if (M == 4) {
-        if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79)) return 2;
+        if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 89)) return 2;
         return (variant >= 30 && variant <= 39) ? 1 : 0;
     }
     if (M == 8 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 0;   // [m][x][k]
@@ -423,6 +423,55 @@ void launch_scan_grouped(int variant, const uint2* gco, int64_t n_alloc, const f
     }
 }
 
+// M = 4 scan over regrouped codes with two-lane slots (256 R codes per workgroup): variants 80..89
+int scan4q_codes_per_slot(int variant, int64_t n_alloc)
+{
+    // (32 and 30 codes per lane-slot spill registers inside the tile loop: 0.49 and 0.61 of the LDS peak against 0.72)
+    switch (variant) {
+        case 81: return 26;
+        case 82: return 28;
+        case 83: return 24;
+        case 84: return 16;
+        default: break;
+    }
+    const int ncu = cu_count();
+    static const int cand[] = {28, 26, 24, 16};
+    int best = 28;
+    int64_t best_cost = INT64_MAX;
+    for (int R : cand) {
+        const int64_t wgs = (n_alloc + 256 * R - 1) / (256 * R);
+        const int64_t cost = ((wgs + ncu - 1) / ncu) * (2 * R + 13);      // 512 R clocks of reads per tile, about 3.3k of fill and barriers
+        if (cost < best_cost) { best_cost = cost; best = R; }
+    }
+    return best;
+}
+
+void launch_scan_grouped_q(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
+                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro)
+{
+    const int R = scan4q_codes_per_slot(variant, n_alloc);
+    const int64_t nwg = (n_alloc + 256 * (int64_t)R - 1) / (256 * (int64_t)R);
+    switch (R) {
+        case 16:
+            hipLaunchKernelGGL((assign_scan4q_kernel<16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
+                               rows, ntiles, assign, dist, ro);
+            break;
+        case 24:
+            hipLaunchKernelGGL((assign_scan4q_kernel<24, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
+                               rows, ntiles, assign, dist, ro);
+            break;
+        case 26:
+            hipLaunchKernelGGL((assign_scan4q_kernel<26, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
+                               rows, ntiles, assign, dist, ro);
+            break;
+
+        default:
+            hipLaunchKernelGGL((assign_scan4q_kernel<28, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
+                               rows, ntiles, assign, dist, ro);
+            break;
+    }
+}
+
 // M = 8 scans over regrouped codes: variants 70..79.  Variant 70 chooses the codes per lane-slot like the M = 4
 // scan does: rounds * (R + 9) with rounds = ceil(workgroups / CUs) (8e6 codes: 11 rounds of 2605 workgroups at
 // R = 24, 10 rounds of 2500 at R = 25, measured 12.2 ms against 11.4 ms at K = 4000).
@@ -480,16 +529,19 @@ pqkm_status regroup_codes8(const uint8_t* codes, int64_t cnt, uint4* gc8, GroupP
 }
 
 // regroup `cnt` codes into gco: three launches on the stream
-pqkm_status regroup_codes(const uint8_t* codes, int64_t cnt, uint2* gco, GroupPlan* plan, hipStream_t st)
+pqkm_status regroup_codes(const uint8_t* codes, int64_t cnt, uint2* gco, GroupPlan* plan, hipStream_t st,
+                          bool blocks_of_16 = false)
 {
     const int64_t na = group_alloc(cnt);
+    if (blocks_of_16)
+        hipLaunchKernelGGL(code_group_clear_kernel, dim3(1024), dim3(256), 0, st, gco, na);
     int64_t g = (cnt + 4095) / 4096;
     if (g > GROUP_MAX_WGS) g = GROUP_MAX_WGS;
     if (g < 1) g = 1;
     hipLaunchKernelGGL(code_class_count_kernel, dim3((unsigned)g), dim3(GROUP_THREADS), 0, st, codes, cnt, plan);
     hipLaunchKernelGGL(code_group_plan_kernel, dim3(1), dim3(1024), 0, st, plan, (int)g);
     hipLaunchKernelGGL(code_group_scatter_kernel, dim3((unsigned)g), dim3(GROUP_THREADS), 0, st, codes, cnt, plan, gco,
-                       na);
+                       na, blocks_of_16 ? 1 : 0);
     return launched();
 }
 
@@ -567,7 +619,8 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     // the regrouped scans address the tile images through one 32-bit buffer offset: below 4 GB of images only
     const int TK = 128 / M;
     const bool img32 = (int64_t)((K + TK - 1) / TK) * TILE_BYTES < (int64_t)0xfff00000;
-    const bool special = (variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79);
+    const bool special = (variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79) ||
+                         (M == 4 && variant >= 80 && variant <= 89);
     if (M == 8) {
         const bool ok8 = img32 && ((uintptr_t)codes & 7) == 0;
         if (special && !ok8) return 0;
@@ -605,7 +658,11 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     }
     return 70;                            // regrouped half-plane scan, codes per lane-slot chosen per launch
 }
-inline bool variant_grouped(int M, int variant) { return (M == 4 || M == 8) && variant >= 70 && variant <= 79; }
+inline bool variant_grouped(int M, int variant)
+{
+    return ((M == 4 || M == 8) && variant >= 70 && variant <= 79) || (M == 4 && variant >= 80 && variant <= 89);
+}
+inline bool variant_two_lane(int M, int variant) { return M == 4 && variant >= 80 && variant <= 89; }
 inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) && variant >= 50 && variant <= 59; }
 
 // The fused iteration's hand-over from the scan to the histogram: filled in by the caller (wanted, KT, ngroups),
@@ -625,7 +682,12 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     constexpr int TK = 128 / M;
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
-    const int variant = effective_variant(M, opt.scan_variant, N, K, codes);
+    int variant = effective_variant(M, opt.scan_variant, N, K, codes);
+    // Many rounds of workgroups and no records to file for the histogram: the scan with two-lane slots, whose
+    // workgroups take twice the codes per tile fill
+    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 23) &&
+        !(link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off))
+        variant = 80;
     const int layout = variant_layout(M, variant);
     const bool sliding = variant_sliding(M, variant);
     if (sliding) {
@@ -670,7 +732,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         // the regrouped copy survives between calls only when one launch covers all codes
         if (grouped && !(reuse_groups && N <= per_launch)) {
             const pqkm_status rs = (M == 8) ? regroup_codes8(codes + n0 * M, cnt, gc8, plan8, st)
-                                            : regroup_codes(codes + n0 * M, cnt, gco, plan, st);
+                                            : regroup_codes(codes + n0 * M, cnt, gco, plan, st, variant_two_lane(M, variant));
             if (rs != PQKM_OK) return PQKM_ERR_DEVICE;
         }
         EventPair ev{};
@@ -682,7 +744,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
                                       dist ? dist + n0 : nullptr, st, rl) != PQKM_OK)
                     return PQKM_ERR_DEVICE;
             }
-        } else if (grouped && M == 8)
+        } else if (variant_two_lane(M, variant))
+            launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
+                                  assign + n0, dist ? dist + n0 : nullptr, st, rl);
+        else if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                  assign + n0, dist ? dist + n0 : nullptr, st, rl);
         else if (grouped && M == 4 && link && link->wanted && variant == 70 && N <= per_launch &&

@@ -674,6 +674,23 @@ __device__ __forceinline__ int64_t group_slot_position(int64_t u, uint32_t slot)
     return (u >> 1) * 8 + ((map >> (4 * slot)) & 15u);
 }
 
+// The same for the scan whose slots are two lanes wide (assign_scan4q_kernel): an LDS access then serves eight
+// slots, {0,1,6,7,10,11,12,13} or {2,3,4,5,8,9,14,15} of a block of 16, of which the even ones read the lower
+// half of their row first and the odd ones the upper: four groups share a block, group 4b + g takes the slots
+// {0,6,10,12}, {1,7,11,13}, {2,4,8,14}, {3,5,9,15}.
+__device__ __forceinline__ int64_t group_slot_position16(int64_t u, uint32_t slot)
+{
+    const uint32_t maps[4] = {0xca60u, 0xdb71u, 0xe842u, 0xf953u};
+    return (u >> 2) * 16 + ((maps[u & 3] >> (4 * slot)) & 15u);
+}
+
+// gco[pos] = (0, ORIGIN_NONE) for every position: the two-lane-slot layout marks its holes this way before the scatter
+__global__ __launch_bounds__(256) void code_group_clear_kernel(uint2* __restrict__ gco, int64_t n_alloc)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_alloc; i += (int64_t)gridDim.x * 256)
+        gco[i] = make_uint2(0u, 0xffffffffu);
+}
+
 // Workgroup w of gridDim.x takes the chunks of 1024 consecutive codes w, w + gridDim.x, ...
 __global__ __launch_bounds__(GROUP_THREADS) void code_class_count_kernel(const uint8_t* __restrict__ codes, int64_t n,
                                                                          GroupPlan* __restrict__ plan)
@@ -805,7 +822,8 @@ __global__ __launch_bounds__(1024) void code_group_plan_kernel(GroupPlan* __rest
 // gco[pos] = (code, original index); positions that receive no code get (0, ORIGIN_NONE)
 __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const uint8_t* __restrict__ codes, int64_t n,
                                                                            const GroupPlan* __restrict__ plan,
-                                                                           uint2* __restrict__ gco, int64_t n_alloc)
+                                                                           uint2* __restrict__ gco, int64_t n_alloc,
+                                                                           int blocks_of_16 = 0)
 {
     __shared__ uint32_t cur[256];
     __shared__ uint32_t first_s[256][GROUP_ROUNDS + 1];
@@ -847,11 +865,12 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
             slot = li / lg;
             u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
         }
-        const int64_t pos = group_slot_position(u, slot);
+        const int64_t pos = blocks_of_16 ? group_slot_position16(u, slot) : group_slot_position(u, slot);
         if (pos < n_alloc) gco[pos] = make_uint2(pk, (uint32_t)i);
     }
     // holes: the empty places of the left-over groups, the second half of the last block of 8, the tail
-    if (blockIdx.x == 0 && tid < 32) {
+    // (blocks of 16: every position was marked empty before this kernel ran)
+    if (blockIdx.x == 0 && tid < 32 && !blocks_of_16) {
         const int64_t T = (int64_t)gtot + lg;
         int64_t pos = -1;
         if (tid < 4) {
@@ -1193,6 +1212,217 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
             const int j = i * THREADS + tid;
             const uint4 r = *reinterpret_cast<const uint4*>(tb + (size_t)j * 32u);
             if (r.z != 0xffffffffu) bo.pool[base + gbase[r.z] + r.w] = make_uint2(r.x, r.y);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 4 scan over residue-grouped codes with slots of TWO lanes (16 centers per lane).
+//
+// Same tile image, same arithmetic and same regrouping idea as assign_scan4p_kernel, but a code is worked on by
+// two lanes instead of four, so a workgroup of 512 threads holds 256 R codes per tile fill instead of 128 R: the
+// 128 KB fill, which the LDS takes at a quarter of its read rate, is shared by twice as many codes.  A lane
+// reads, per subspace, two 16-byte pieces of each of the two half planes: the 32 bytes of its slot's half of the
+// 64-byte plane row first, then (address ^ 32) the other half.  An LDS access serves eight slots; the four even
+// ones are one residue group (four different subcodes mod 4 in every subspace) and start with the lower halves,
+// the four odd ones are another and start with the upper halves: sixteen different 16-byte positions in every
+// read.  Per code and lane the state is what the four-lane scan keeps (two registers of packed row offsets, the
+// running minimum, the tile in which it last improved); the winner inside the tile is recovered in the epilogue.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan4q_kernel(int64_t N, const uint2* __restrict__ gco,
+                                                                const float4* __restrict__ img,
+                                                                const float4* __restrict__ rows, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist, RankOut ro)
+{
+    constexpr int LPS = 2, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr uint32_t HPLANE = 16384;      // bytes per (m, h) plane: 256 subcodes x 16 centers
+    static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+    static_assert(R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+    static_assert(R % 2 == 0, "the epilogue gives every lane R / 2 codes");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid & 1;
+    const int c = tid >> 1;
+    const uint32_t hq = ((uint32_t)(c & 1) << 5) | ((uint32_t)q << 4);    // the slot's first half of the row, the lane's piece
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t low15 = 0x7fffu;
+
+    uint32_t pa[R], pb[R];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        const uint32_t pk = gco[n].x;
+        const uint32_t f0 = ((pk & 255u) << 6) | hq;
+        const uint32_t f1 = (((pk >> 8) & 255u) << 6) | hq;
+        const uint32_t f2 = ((((pk >> 16) & 255u) << 6) | hq) + 65536u;
+        const uint32_t f3 = (((pk >> 24) << 6) | hq) + 65536u;
+        pa[r] = f0 | (f2 << 15);
+        pb[r] = f1 | (f3 << 15);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    // a step is one subspace of one code: four 16-byte reads (two pieces of each half plane)
+    struct Quad { float4 a, b, c, d; };
+    auto issue = [&](int step) -> Quad {
+        const int r = step / 4, m = step % 4;
+        const uint32_t ad = (m == 0) ? unpack_low15(low15, pa[r])
+                          : (m == 1) ? unpack_low15(low15, pb[r])
+                          : (m == 2) ? unpack_high17(pa[r])
+                                     : unpack_high17(pb[r]);
+        const uint32_t ad2 = ad ^ 32u;
+        const uint32_t po = (m & 1) ? 2 * HPLANE : 0;
+        Quad p;
+        p.a = lds_read16(tb, ad + po);
+        p.b = lds_read16(tb, ad2 + po);
+        p.c = lds_read16(tb, ad + po + HPLANE);
+        p.d = lds_read16(tb, ad2 + po + HPLANE);
+        return p;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        Quad ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+        float4 sa, sb, sc, sd;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int step = 4 * r + m;
+                const Quad cur = ring[step % DEPTH];
+                if (step + DEPTH < 4 * R) ring[step % DEPTH] = issue(step + DEPTH);
+                if (m == 0) {
+                    sa = cur.a; sb = cur.b; sc = cur.c; sd = cur.d;
+                } else {
+                    sa.x = sa.x + cur.a.x; sa.y = sa.y + cur.a.y; sa.z = sa.z + cur.a.z; sa.w = sa.w + cur.a.w;
+                    sb.x = sb.x + cur.b.x; sb.y = sb.y + cur.b.y; sb.z = sb.z + cur.b.z; sb.w = sb.w + cur.b.w;
+                    sc.x = sc.x + cur.c.x; sc.y = sc.y + cur.c.y; sc.z = sc.z + cur.c.z; sc.w = sc.w + cur.c.w;
+                    sd.x = sd.x + cur.d.x; sd.y = sd.y + cur.d.y; sd.z = sd.z + cur.d.z; sd.w = sd.w + cur.d.w;
+                }
+                if (m == 3) {
+                    float m16 = min3_f32(sa.x, sa.y, sa.z);
+                    m16 = min3_f32(m16, sa.w, sb.x);
+                    m16 = min3_f32(m16, sb.y, sb.z);
+                    m16 = min3_f32(m16, sb.w, sc.x);
+                    m16 = min3_f32(m16, sc.y, sc.z);
+                    m16 = min3_f32(m16, sc.w, sd.x);
+                    m16 = min3_f32(m16, sd.y, sd.z);
+                    const float nb = min3_f32(m16, sd.w, best[r]);
+                    tix[r] = (nb < best[r]) ? t : tix[r];
+                    best[r] = nb;
+                }
+            }
+        }
+    }
+
+    // Epilogue, transposed through LDS as in assign_scan4p_kernel: every lane leaves (minimum, tile) per code, then
+    // lane l finishes the codes l, l + THREADS, ...: the slot minimum is the smaller of the two lanes' minima, the
+    // winning tile the lowest tile among the lanes that attain it, and for every lane position that attains it in
+    // that tile the 16 sums of its centers are rebuilt from the row-ordered copy of the images ([tile][m][x][32
+    // centers]: same bits, same order of additions) and the lowest center index with that sum is kept.
+    constexpr int CPL = R / 2;
+    __syncthreads();
+    {
+        float2* rec = reinterpret_cast<float2*>(tile);
+#pragma unroll
+        for (int r = 0; r < R; ++r)                  // record index = 2 * (code index in the workgroup) + q
+            rec[(r * SLOTS + c) * 2 + q] = make_float2(best[r], __builtin_bit_cast(float, tix[r]));
+    }
+    __syncthreads();
+    __amdgpu_buffer_rsrc_t rs_img = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(rows), 0, (uint32_t)ntiles * (uint32_t)TILE_BYTES, 0x00020000);
+    constexpr int TNONE = 0x7fffffff;
+#pragma unroll 1
+    for (int i0 = 0; i0 < CPL; ++i0) {
+        const int jj = i0 * THREADS + tid;           // code index in the workgroup: slot jj % SLOTS, round jj / SLOTS
+        int64_t n = base + jj;
+        const bool live = n < N;
+        if (!live) n = N - 1;
+        const float4 ra = lds_read16(tb, (uint32_t)jj * 16u);
+        const float b0 = ra.x, b1 = ra.z;
+        const int t0 = __builtin_bit_cast(int, ra.y), t1 = __builtin_bit_cast(int, ra.w);
+        const float sm = __builtin_fminf(b0, b1);
+        const int c0 = (b0 == sm && t0 >= 0) ? t0 : TNONE, c1 = (b1 == sm && t1 >= 0) ? t1 : TNONE;
+        const int tm = c0 < c1 ? c0 : c1;
+        uint32_t cand = (uint32_t)(c0 == tm) | ((uint32_t)(c1 == tm) << 1);
+        if (tm == TNONE || !live) cand = 0u;
+        const uint2 g = gco[n];
+        const uint32_t pk = g.x;
+        const uint32_t og = live ? g.y : ORIGIN_NONE;
+        const uint32_t hs = (uint32_t)((jj % SLOTS) & 1);      // which half of the row the code's slot read first
+        int bi = IDX_NONE;
+        while (__any(cand != 0u)) {                  // one trip unless the two lane positions tie exactly
+            const uint32_t qe = cand ? (uint32_t)__builtin_ctz(cand) : 0u;
+            // lane position qe of a slot with first half hs owns the pieces p = 2 hs' + qe of both halves of the row:
+            // first read hs' = hs (centers 4 p .. 4 p + 3 and 16 + 4 p ..), second read hs' = 1 - hs
+            const uint32_t pA = 2u * hs + qe, pB = 2u * (1u - hs) + qe;
+            const uint32_t tb0 = cand ? (uint32_t)tm * (uint32_t)TILE_BYTES : 0xfff00000u;
+            v4f sA, sB, sC, sD;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t x = (pk >> (8 * m)) & 255u;
+                const uint32_t o = tb0 + (x << 7);
+                constexpr int MP = 32768;             // bytes per subspace in a tile of the row copy
+                const v4f vA = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pA * 16u, m * MP, 0));
+                const v4f vB = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pB * 16u, m * MP, 0));
+                const v4f vC = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pA * 16u, m * MP + 64, 0));
+                const v4f vD = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pB * 16u, m * MP + 64, 0));
+                if (m == 0) { sA = vA; sB = vB; sC = vC; sD = vD; }
+                else { sA = sA + vA; sB = sB + vB; sC = sC + vC; sD = sD + vD; }
+            }
+            if (cand) {
+                const int kt = tm * TK;
+                const int kA = kt + (int)pA * 4, kB = kt + (int)pB * 4, kC = kA + 16, kD = kB + 16;
+                int k = IDX_NONE;
+                auto take = [&](const v4f& v, int k0) {
+                    int kk = IDX_NONE;
+                    if (v.w == sm) kk = k0 + 3;
+                    if (v.z == sm) kk = k0 + 2;
+                    if (v.y == sm) kk = k0 + 1;
+                    if (v.x == sm) kk = k0;
+                    k = kk < k ? kk : k;
+                };
+                take(sA, kA); take(sB, kB); take(sC, kC); take(sD, kD);
+                bi = k < bi ? k : bi;
+                cand &= cand - 1u;
+            }
+        }
+        if (og != ORIGIN_NONE) {
+            const int kw = (bi == IDX_NONE) ? 0 : bi;
+            assign[og] = kw;
+            if (dist) dist[og] = sm;
+            if (ro.count) ro.rank[og] = atomicAdd(&ro.count[kw], 1u);
         }
     }
 }
