@@ -86,7 +86,7 @@ inline bool tiled_M(int M) { return M == 4 || M == 8 || M == 16 || M == 32; }
 struct Carve {
     size_t img_off, img_bytes, hist_off, hist_bytes, counts_off, counts_bytes, parts_off, parts_bytes, gid_off,
         gid_bytes, gco_off, plan_off, rows_off, gc8_off, plan8_off, sidx_off, seg_off, pool_off, bseg_off, skew_off,
-        rank_off, total;
+        rank_off, tabt_off, rowoff_off, total;
 };
 
 // The regrouped copy of the codes (M = 4 scan) covers one scan launch of at most this many codes.
@@ -181,6 +181,14 @@ Carve carve(int64_t N, int M, int K)
         off += align256((size_t)na * sizeof(uint4));
         c.plan8_off = off;
         off += align256(sizeof(GroupPlan8));
+    }
+    // table-built tiles (M = 4): transposed tables with a row of +inf, row offsets of the centers per tile and plane
+    c.tabt_off = c.rowoff_off = off;
+    if (M == 4) {
+        c.tabt_off = off;
+        off += align256(((size_t)M * L + 1) * L * sizeof(float));
+        c.rowoff_off = off;
+        off += align256((((size_t)K + 31) / 32) * 128 * sizeof(uint32_t));
     }
     // subcode words of the sliding-window scan (M = 16, 32): M/4 + 1 words per code position of one launch
     c.skew_off = off;
@@ -301,7 +309,7 @@ void launch_scan_skew(const uint8_t* codes, int64_t N, const float4* img, int nt
 inline int variant_layout(int M, int variant)
 {
     if (M == 4) {
-        if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 89)) return 2;
+        if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 99)) return 2;
         return (variant >= 30 && variant <= 39) ? 1 : 0;
     }
     if (M == 8 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 0;   // [m][x][k]
@@ -447,10 +455,31 @@ int scan4q_codes_per_slot(int variant, int64_t n_alloc)
 }
 
 void launch_scan_grouped_q(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
-                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro)
+                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro, TileSource ts)
 {
-    const int R = scan4q_codes_per_slot(variant, n_alloc);
+    const int R = scan4q_codes_per_slot(variant >= 90 ? variant - 10 : variant, n_alloc);
     const int64_t nwg = (n_alloc + 256 * (int64_t)R - 1) / (256 * (int64_t)R);
+    if (ts.tabT) {
+        switch (R) {
+            case 16:
+                hipLaunchKernelGGL((assign_scan4q_kernel<16, 512, 2, true>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc,
+                                   gco, img, rows, ntiles, assign, dist, ro, ts);
+                break;
+            case 24:
+                hipLaunchKernelGGL((assign_scan4q_kernel<24, 512, 2, true>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc,
+                                   gco, img, rows, ntiles, assign, dist, ro, ts);
+                break;
+            case 26:
+                hipLaunchKernelGGL((assign_scan4q_kernel<26, 512, 2, true>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc,
+                                   gco, img, rows, ntiles, assign, dist, ro, ts);
+                break;
+            default:
+                hipLaunchKernelGGL((assign_scan4q_kernel<28, 512, 2, true>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc,
+                                   gco, img, rows, ntiles, assign, dist, ro, ts);
+                break;
+        }
+        return;
+    }
     switch (R) {
         case 16:
             hipLaunchKernelGGL((assign_scan4q_kernel<16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
@@ -620,7 +649,7 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     const int TK = 128 / M;
     const bool img32 = (int64_t)((K + TK - 1) / TK) * TILE_BYTES < (int64_t)0xfff00000;
     const bool special = (variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79) ||
-                         (M == 4 && variant >= 80 && variant <= 89);
+                         (M == 4 && variant >= 80 && variant <= 99);
     if (M == 8) {
         const bool ok8 = img32 && ((uintptr_t)codes & 7) == 0;
         if (special && !ok8) return 0;
@@ -660,9 +689,10 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
 }
 inline bool variant_grouped(int M, int variant)
 {
-    return ((M == 4 || M == 8) && variant >= 70 && variant <= 79) || (M == 4 && variant >= 80 && variant <= 89);
+    return ((M == 4 || M == 8) && variant >= 70 && variant <= 79) || (M == 4 && variant >= 80 && variant <= 99);
 }
-inline bool variant_two_lane(int M, int variant) { return M == 4 && variant >= 80 && variant <= 89; }
+inline bool variant_two_lane(int M, int variant) { return M == 4 && variant >= 80 && variant <= 99; }
+inline bool variant_table_tiles(int M, int variant) { return M == 4 && variant >= 90 && variant <= 99; }
 inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) && variant >= 50 && variant <= 59; }
 
 // The fused iteration's hand-over from the scan to the histogram: filled in by the caller (wanted, KT, ngroups),
@@ -716,6 +746,18 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
     uint4* gc8 = reinterpret_cast<uint4*>(ws + c.gc8_off);
     GroupPlan8* plan8 = reinterpret_cast<GroupPlan8*>(ws + c.plan8_off);
+    // tiles built in the kernel from the transposed tables: the tables and the centers' row offsets, once per call
+    TileSource tsrc{};
+    if (variant_table_tiles(M, variant)) {
+        float* tabT = reinterpret_cast<float*>(ws + c.tabt_off);
+        uint32_t* rowoff = reinterpret_cast<uint32_t*>(ws + c.rowoff_off);
+        hipLaunchKernelGGL(transpose_tables_kernel, dim3(L, (unsigned)M + 1), dim3(256), 0, st, tables, M, tabT);
+        const int64_t nro = ntiles * 128;
+        hipLaunchKernelGGL(tile_rows4_kernel, dim3((unsigned)((nro + 255) / 256)), dim3(256), 0, st, centers, K, rowoff, nro);
+        tsrc.tabT = tabT;
+        tsrc.rowoff = rowoff;
+        tsrc.tab_bytes = (uint32_t)(((size_t)M * L + 1) * L * sizeof(float));
+    }
     // ranks for the sorted-path histogram: from the scans that finish their codes one per lane (the regrouped scans
     // and the sliding-window scan), unless this iteration already hands records over by cluster group
     RankOut ro{};
@@ -746,7 +788,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             }
         } else if (variant_two_lane(M, variant))
             launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
-                                  assign + n0, dist ? dist + n0 : nullptr, st, rl);
+                                  assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc);
         else if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                  assign + n0, dist ? dist + n0 : nullptr, st, rl);

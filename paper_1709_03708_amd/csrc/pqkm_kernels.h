@@ -1217,6 +1217,35 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
 }
 
 // ---------------------------------------------------------------------------------------------
+// Inputs of the table-built tiles (see TileSource): tabT[m][c][x] = tables[m][x][c] with one extra row of +inf, and
+// the byte offsets of the centers' rows per tile and half plane.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_tables_kernel(const float* __restrict__ tables, int M,
+                                                               float* __restrict__ tabT)
+{
+    // grid (256 subcodes c, M + 1): row (m, c) of the transposed tables; the row after the last table is +inf
+    const int c = blockIdx.x, m = blockIdx.y, x = threadIdx.x;
+    if (m == M) {
+        if (c == 0) tabT[(size_t)M * L * L + x] = INFINITY;
+        return;
+    }
+    tabT[((size_t)m * L + c) * L + x] = tables[((size_t)m * L + x) * L + c];
+}
+
+// rowoff[tile][2 m + h][kin] for M = 4, tiles of 32 centers: one thread per entry
+__global__ __launch_bounds__(256) void tile_rows4_kernel(const uint8_t* __restrict__ centers, int K,
+                                                         uint32_t* __restrict__ rowoff, int64_t total)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int kin = (int)(e & 15), pl = (int)((e >> 4) & 7);
+    const int64_t tile = e >> 7;
+    const int m = pl >> 1, h = pl & 1;
+    const int64_t k = tile * 32 + 16 * h + kin;
+    rowoff[e] = (k < K) ? (uint32_t)(m * L + centers[k * 4 + m]) * 1024u : (uint32_t)(4 * L) * 1024u;
+}
+
+// ---------------------------------------------------------------------------------------------
 // M = 4 scan over residue-grouped codes with slots of TWO lanes (16 centers per lane).
 //
 // Same tile image, same arithmetic and same regrouping idea as assign_scan4p_kernel, but a code is worked on by
@@ -1229,12 +1258,25 @@ __global__ __launch_bounds__(THREADS) void assign_scan4p_kernel(const uint8_t* _
 // read.  Per code and lane the state is what the four-lane scan keeps (two registers of packed row offsets, the
 // running minimum, the tile in which it last improved); the winner inside the tile is recovered in the epilogue.
 // ---------------------------------------------------------------------------------------------
-template <int R, int THREADS, int DEPTH>
+// Where the tiles come from when they are not read as ready-made images: the transposed tables
+// tabT[m][c][x] = A^m[x][c] (one contiguous 1 KB row per center subcode, plus one last row of +inf) and, per tile and
+// half plane, the byte offsets of the rows of its 16 centers, rowoff[tile][2 m + h][16] (the +inf row for centers
+// past K).  The tables are small enough (M x 256 KB) to stay in every L2, so a tile costs no HBM traffic at all,
+// where the images (K x M KB, fetched again by every workgroup that has drifted out of step with its neighbours)
+// cost the scan its whole HBM traffic.
+struct TileSource {
+    const float* tabT = nullptr;
+    const uint32_t* rowoff = nullptr;
+    uint32_t tab_bytes = 0;
+};
+
+template <int R, int THREADS, int DEPTH, bool TABLES = false>
 __global__ __launch_bounds__(THREADS) void assign_scan4q_kernel(int64_t N, const uint2* __restrict__ gco,
                                                                 const float4* __restrict__ img,
                                                                 const float4* __restrict__ rows, int ntiles,
                                                                 int32_t* __restrict__ assign,
-                                                                float* __restrict__ dist, RankOut ro)
+                                                                float* __restrict__ dist, RankOut ro,
+                                                                TileSource ts = TileSource{})
 {
     constexpr int LPS = 2, TK = 32;
     constexpr int SLOTS = THREADS / LPS;
@@ -1280,9 +1322,43 @@ __global__ __launch_bounds__(THREADS) void assign_scan4q_kernel(int64_t N, const
             const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
         return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
     };
+    // TABLES: float4 i*THREADS + tid of the tile is plane i/2, subcode x = (i&1)*128 + tid/4, piece p = tid&3: its four
+    // entries are A^m[x][c] of the centers 16h + 4p + j, i.e. element x of four rows of the transposed tables
+    const uint32_t x4 = (uint32_t)(tid >> 2) * 4u;
+    const uint32_t ro_lane = (uint32_t)(tid & 3) * 16u;
+    auto ro_load = [&](int t, int pl) -> uint4 {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint32_t*>(ts.rowoff + (size_t)t * 128), 0, 512, 0x00020000);
+        return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, ro_lane, pl * 64, 0));
+    };
+    __amdgpu_buffer_rsrc_t rs_tab = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(ts.tabT), 0, ts.tab_bytes,
+                                                                      0x00020000);
     v4f pf[NF];
+    auto plane_load = [&](const uint4 rof, int pl) {
+        const uint32_t o0 = rof.x + x4, o1 = rof.y + x4, o2 = rof.z + x4, o3 = rof.w + x4;
+        pf[2 * pl].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o0, 0, 0));
+        pf[2 * pl].y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o1, 0, 0));
+        pf[2 * pl].z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o2, 0, 0));
+        pf[2 * pl].w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o3, 0, 0));
+        pf[2 * pl + 1].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o0, 512, 0));
+        pf[2 * pl + 1].y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o1, 512, 0));
+        pf[2 * pl + 1].z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o2, 512, 0));
+        pf[2 * pl + 1].w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_tab, o3, 512, 0));
+    };
+    uint4 rnext = make_uint4(0u, 0u, 0u, 0u);      // row offsets of the plane whose loads are issued next
+    if (TABLES) {
+        static_assert(!TABLES || (THREADS == 512 && NF == 16), "the table-built tile assumes 512 threads");
+        rnext = ro_load(0, 0);
 #pragma unroll
-    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+        for (int pl = 0; pl < 8; ++pl) {
+            const uint4 cur = rnext;
+            rnext = pl < 7 ? ro_load(0, pl + 1) : ro_load(ntiles > 1 ? 1 : 0, 0);
+            plane_load(cur, pl);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+    }
 
     // a step is one subspace of one code: four 16-byte reads (two pieces of each half plane)
     struct Quad { float4 a, b, c, d; };
@@ -1312,11 +1388,24 @@ __global__ __launch_bounds__(THREADS) void assign_scan4q_kernel(int64_t N, const
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
         float4 sa, sb, sc, sd;
+        const int tnn = tn + 1 < ntiles ? tn + 1 : tn;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
+            if (TABLES) {
+                // the eight planes of the next tile, spread over the first 5/8 of the scan; with each the row
+                // offsets of the plane after it (those of plane 0 of the tile after next come with plane 7)
 #pragma unroll
-            for (int i = 0; i < NF; ++i)
-                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+                for (int pl = 0; pl < 8; ++pl)
+                    if ((2 * pl * R * 5) / (NF * 8) == r) {
+                        const uint4 cur = rnext;
+                        rnext = pl < 7 ? ro_load(tn, pl + 1) : ro_load(tnn, 0);
+                        plane_load(cur, pl);
+                    }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NF; ++i)
+                    if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+            }
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const int step = 4 * r + m;

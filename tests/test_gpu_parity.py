@@ -99,7 +99,7 @@ def test_assign_every_compiled_shape(env, variant):
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [70, 71, 72, 73, 74, 75, 76, 80, 81, 82, 83, 84])
+@pytest.mark.parametrize("variant", [70, 71, 72, 73, 74, 75, 76, 80, 81, 82, 83, 84, 90, 91, 92, 93, 94])
 @pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 200003), ("uniform", 4093), ("uniform", 7),
                                     ("uniform", 1), ("one_class", 5000), ("two_classes", 6001), ("latin", 8192)])
 def test_assign_regrouped_scan(env, variant, kind, N):
@@ -125,7 +125,7 @@ def test_assign_regrouped_scan(env, variant, kind, N):
             codes = (codes & 0xFC) | lat
     tables = env["oracle"].build_tables(W.codewords(w))
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
-    if variant in (70, 80):
+    if variant in (70, 80, 90):
         ham = np.ones((4, 256, 256), np.float32)
         for m in range(4):
             np.fill_diagonal(ham[m], 0)
