@@ -312,7 +312,7 @@ inline int variant_layout(int M, int variant)
         if ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 99)) return 2;
         return (variant >= 30 && variant <= 39) ? 1 : 0;
     }
-    if (M == 8 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79))) return 0;   // [m][x][k]
+    if (M == 8 && ((variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 84))) return 0;   // [m][x][k]
     return variant != 1 ? 1 : 0;  // M = 8, 16, 32: every other shape but 1 (the unskewed tiled scan) is skewed
 }
 
@@ -544,16 +544,62 @@ void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const 
     }
 }
 
+// M = 8 scan over regrouped codes with two-lane slots (256 R codes per workgroup): variants 80..84
+void launch_scan_grouped8_q(int variant, const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles,
+                            int32_t* assign, float* dist, hipStream_t st, RankOut ro)
+{
+    int R = 0;
+    switch (variant) {
+        case 81: R = 24; break;
+        case 82: R = 22; break;
+        case 83: R = 20; break;
+        case 84: R = 16; break;
+        default: {
+            const int ncu = cu_count();
+            static const int cand[] = {24, 22, 20, 16};
+            int64_t best_cost = INT64_MAX;
+            for (int r : cand) {
+                const int64_t wgs = (n_alloc + 256 * r - 1) / (256 * r);
+                const int64_t cost = ((wgs + ncu - 1) / ncu) * (2 * r + 13);
+                if (cost < best_cost) { best_cost = cost; R = r; }
+            }
+        }
+    }
+    const int64_t nwg = (n_alloc + 256 * (int64_t)R - 1) / (256 * (int64_t)R);
+    switch (R) {
+        case 16:
+            hipLaunchKernelGGL((assign_scan8q_kernel<16, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
+                               ntiles, assign, dist, ro);
+            break;
+        case 20:
+            hipLaunchKernelGGL((assign_scan8q_kernel<20, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
+                               ntiles, assign, dist, ro);
+            break;
+        case 22:
+            hipLaunchKernelGGL((assign_scan8q_kernel<22, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
+                               ntiles, assign, dist, ro);
+            break;
+        default:
+            hipLaunchKernelGGL((assign_scan8q_kernel<24, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
+                               ntiles, assign, dist, ro);
+            break;
+    }
+}
+
 // the same for 64-bit codes: zero the class counters, count, plan, scatter
-pqkm_status regroup_codes8(const uint8_t* codes, int64_t cnt, uint4* gc8, GroupPlan8* plan, hipStream_t st)
+pqkm_status regroup_codes8(const uint8_t* codes, int64_t cnt, uint4* gc8, GroupPlan8* plan, hipStream_t st,
+                           bool blocks_of_16 = false)
 {
     const int64_t na = group_alloc(cnt);
+    if (blocks_of_16)
+        hipLaunchKernelGGL(code8_group_clear_kernel, dim3(1024), dim3(256), 0, st, gc8, na);
     hipLaunchKernelGGL(zero_u32_kernel, dim3(64), dim3(256), 0, st, plan->count, (int64_t)GROUP8_CLASSES);
     unsigned g = (unsigned)((cnt + 1023) / 1024 < 4096 ? (cnt + 1023) / 1024 : 4096);
     if (g < 1) g = 1;
     hipLaunchKernelGGL(code8_class_count_kernel, dim3(g), dim3(256), 0, st, codes, cnt, plan);
     hipLaunchKernelGGL(code8_group_plan_kernel, dim3(1), dim3(1024), 0, st, plan);
-    hipLaunchKernelGGL(code8_group_scatter_kernel, dim3(g), dim3(256), 0, st, codes, cnt, plan, gc8, na);
+    hipLaunchKernelGGL(code8_group_scatter_kernel, dim3(g), dim3(256), 0, st, codes, cnt, plan, gc8, na,
+                       blocks_of_16 ? 1 : 0);
     return launched();
 }
 
@@ -649,11 +695,13 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     const int TK = 128 / M;
     const bool img32 = (int64_t)((K + TK - 1) / TK) * TILE_BYTES < (int64_t)0xfff00000;
     const bool special = (variant >= 40 && variant <= 49) || (variant >= 70 && variant <= 79) ||
-                         (M == 4 && variant >= 80 && variant <= 99);
+                         (M == 4 && variant >= 80 && variant <= 99) || (M == 8 && variant >= 80 && variant <= 84);
     if (M == 8) {
         const bool ok8 = img32 && ((uintptr_t)codes & 7) == 0;
         if (special && !ok8) return 0;
         // 65536 residue classes: regrouping pays once most classes hold a few dozen codes
+        // (two lanes per code, variants 80..84, are no faster here: an LDS access then holds two groups of four codes, and
+        // with 12 % of the groups left over from the matching its conflicts double: 0.61 of the LDS peak either way)
         if (variant == 0 && ok8 && K >= 256 && N >= ((int64_t)1 << 22)) return 70;
         if (variant == 0) {
             // skewed scan: while one round of workgroups covers the codes, the smallest shape that does so (measured
@@ -689,9 +737,13 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
 }
 inline bool variant_grouped(int M, int variant)
 {
-    return ((M == 4 || M == 8) && variant >= 70 && variant <= 79) || (M == 4 && variant >= 80 && variant <= 99);
+    return ((M == 4 || M == 8) && variant >= 70 && variant <= 79) || (M == 4 && variant >= 80 && variant <= 99) ||
+           (M == 8 && variant >= 80 && variant <= 84);
 }
-inline bool variant_two_lane(int M, int variant) { return M == 4 && variant >= 80 && variant <= 99; }
+inline bool variant_two_lane(int M, int variant)
+{
+    return (M == 4 && variant >= 80 && variant <= 99) || (M == 8 && variant >= 80 && variant <= 84);
+}
 inline bool variant_table_tiles(int M, int variant) { return M == 4 && variant >= 90 && variant <= 99; }
 inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) && variant >= 50 && variant <= 59; }
 
@@ -773,7 +825,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         const RankOut rl{ro.count, ro.count ? ro.rank + n0 : nullptr};
         // the regrouped copy survives between calls only when one launch covers all codes
         if (grouped && !(reuse_groups && N <= per_launch)) {
-            const pqkm_status rs = (M == 8) ? regroup_codes8(codes + n0 * M, cnt, gc8, plan8, st)
+            const pqkm_status rs = (M == 8) ? regroup_codes8(codes + n0 * M, cnt, gc8, plan8, st, variant_two_lane(M, variant))
                                             : regroup_codes(codes + n0 * M, cnt, gco, plan, st, variant_two_lane(M, variant));
             if (rs != PQKM_OK) return PQKM_ERR_DEVICE;
         }
@@ -786,7 +838,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
                                       dist ? dist + n0 : nullptr, st, rl) != PQKM_OK)
                     return PQKM_ERR_DEVICE;
             }
-        } else if (variant_two_lane(M, variant))
+        } else if (M == 8 && variant_two_lane(M, variant))
+            launch_scan_grouped8_q(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
+                                   assign + n0, dist ? dist + n0 : nullptr, st, rl);
+        else if (variant_two_lane(M, variant))
             launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc);
         else if (grouped && M == 8)

@@ -1712,7 +1712,8 @@ __global__ __launch_bounds__(1024) void code8_group_plan_kernel(GroupPlan8* __re
 // gc8[pos] = (code low word, code high word, original index, 0); positions that receive no code get ORIGIN_NONE
 __global__ __launch_bounds__(256) void code8_group_scatter_kernel(const uint8_t* __restrict__ codes, int64_t n,
                                                                   GroupPlan8* __restrict__ plan,
-                                                                  uint4* __restrict__ gc8, int64_t n_alloc)
+                                                                  uint4* __restrict__ gc8, int64_t n_alloc,
+                                                                  int blocks_of_16 = 0)
 {
     const uint2* cw = reinterpret_cast<const uint2*>(codes);
     const uint32_t gtot = plan->groups, ltot = plan->leftovers, lg = plan->lgroups, dm1 = plan->period_m1;
@@ -1743,10 +1744,11 @@ __global__ __launch_bounds__(256) void code8_group_scatter_kernel(const uint8_t*
             slot = li / lg;
             u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
         }
-        const int64_t pos = group_slot_position(u, slot);
+        const int64_t pos = blocks_of_16 ? group_slot_position16(u, slot) : group_slot_position(u, slot);
         if (pos < n_alloc) gc8[pos] = make_uint4(v.x, v.y, (uint32_t)i, 0u);
     }
-    if (blockIdx.x == 0 && threadIdx.x < 32) {
+    // holes (blocks of 16: every position was marked empty before this kernel ran)
+    if (blockIdx.x == 0 && threadIdx.x < 32 && !blocks_of_16) {
         const int tid = threadIdx.x;
         const int64_t T = (int64_t)gtot + lg;
         int64_t pos = -1;
@@ -1942,6 +1944,193 @@ __global__ __launch_bounds__(THREADS) void assign_scan8p_kernel(const uint8_t* _
             assign[dst] = kw;
             if (dist) dist[dst] = sm;
             if (ro.count) ro.rank[dst] = atomicAdd(&ro.count[kw], 1u);
+        }
+    }
+}
+
+// gc8[pos] = (0, 0, ORIGIN_NONE, 0) for every position: the two-lane-slot layout marks its holes before the scatter
+__global__ __launch_bounds__(256) void code8_group_clear_kernel(uint4* __restrict__ gc8, int64_t n_alloc)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_alloc; i += (int64_t)gridDim.x * 256)
+        gc8[i] = make_uint4(0u, 0u, 0xffffffffu, 0u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// M = 8 scan over residue-grouped codes with slots of two lanes (8 centers per lane): what
+// assign_scan4q_kernel is to assign_scan4p_kernel.  Same image (img[tile][m][x][16]) and arithmetic as
+// assign_scan8p_kernel; a lane reads, per subspace, the 16-byte piece of its slot's half of the 64-byte row and
+// then (address ^ 32) the piece of the other half; even slots start with the lower half, odd slots with the upper;
+// a workgroup of 512 threads holds 256 R codes per tile fill instead of 128 R.
+// ---------------------------------------------------------------------------------------------
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan8q_kernel(int64_t N, const uint4* __restrict__ gc8,
+                                                                const float4* __restrict__ img, int ntiles,
+                                                                int32_t* __restrict__ assign,
+                                                                float* __restrict__ dist, RankOut ro)
+{
+    constexpr int LPS = 2, TK = 16, M = 8;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr int NF = TILE_F4 / THREADS;
+    constexpr uint32_t PLANE = 16384;       // bytes per subspace plane: 256 subcodes x 16 centers
+    static_assert(TILE_F4 % THREADS == 0, "tile must divide evenly over the workgroup");
+    static_assert(R * THREADS * 8 <= TILE_BYTES, "the per-lane records must fit the tile buffer");
+    static_assert(R % 2 == 0, "the epilogue gives every lane R / 2 codes");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid & 1;
+    const int c = tid >> 1;
+    const uint32_t hq = ((uint32_t)(c & 1) << 5) | ((uint32_t)q << 4);
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t low15 = 0x7fffu;
+
+    uint32_t fld[R][4];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        const uint4 g = gc8[n];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t xa = (g.x >> (8 * w)) & 255u, xb = (g.y >> (8 * w)) & 255u;
+            fld[r][w] = ((xa << 6) | hq) | ((((xb << 6) | hq) + 65536u) << 15);
+        }
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    v4f* ltile = reinterpret_cast<v4f*>(tile);
+    auto gload = [&](int t, int i) -> v4f {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float4*>(img + (size_t)t * TILE_F4), 0, TILE_BYTES, 0x00020000);
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, i * THREADS * 16, 0));
+    };
+    v4f pf[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) pf[i] = gload(0, i);
+
+    struct Pair { float4 a, b; };
+    auto issue = [&](int step) -> Pair {
+        const int r = step / M, m = step % M;
+        const uint32_t ad = (m < 4) ? unpack_low15(low15, fld[r][m]) : unpack_high17(fld[r][m - 4]);
+        const uint32_t po = (uint32_t)(m & 3) * PLANE;
+        Pair p;
+        p.a = lds_read16(tb, ad + po);
+        p.b = lds_read16(tb, (ad ^ 32u) + po);
+        return p;
+    };
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NF; ++i) ltile[i * THREADS + tid] = pf[i];
+        __syncthreads();
+        const int tn = t + 1 < ntiles ? t + 1 : t;
+        Pair ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+        float4 sa, sb;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+                if ((i * R * 5) / (NF * 8) == r) pf[i] = gload(tn, i);
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const int step = M * r + m;
+                const Pair cur = ring[step % DEPTH];
+                if (step + DEPTH < M * R) ring[step % DEPTH] = issue(step + DEPTH);
+                if (m == 0) {
+                    sa = cur.a;
+                    sb = cur.b;
+                } else {
+                    sa.x = sa.x + cur.a.x; sa.y = sa.y + cur.a.y; sa.z = sa.z + cur.a.z; sa.w = sa.w + cur.a.w;
+                    sb.x = sb.x + cur.b.x; sb.y = sb.y + cur.b.y; sb.z = sb.z + cur.b.z; sb.w = sb.w + cur.b.w;
+                }
+                if (m == M - 1) {
+                    float m8 = min3_f32(sa.x, sa.y, sa.z);
+                    m8 = min3_f32(m8, sa.w, sb.x);
+                    m8 = min3_f32(m8, sb.y, sb.z);
+                    const float nb = min3_f32(m8, sb.w, best[r]);
+                    tix[r] = (nb < best[r]) ? t : tix[r];
+                    best[r] = nb;
+                }
+            }
+        }
+    }
+
+    // Epilogue, transposed through LDS: lane l finishes the codes l, l + THREADS, ...
+    constexpr int CPL = R / 2;
+    __syncthreads();
+    {
+        float2* rec = reinterpret_cast<float2*>(tile);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            rec[(r * SLOTS + c) * 2 + q] = make_float2(best[r], __builtin_bit_cast(float, tix[r]));
+    }
+    __syncthreads();
+    __amdgpu_buffer_rsrc_t rs_img = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(img), 0, (uint32_t)ntiles * (uint32_t)TILE_BYTES, 0x00020000);
+    constexpr int TNONE = 0x7fffffff;
+#pragma unroll 1
+    for (int i0 = 0; i0 < CPL; ++i0) {
+        const int jj = i0 * THREADS + tid;
+        int64_t n = base + jj;
+        const bool live = n < N;
+        if (!live) n = N - 1;
+        const float4 ra = lds_read16(tb, (uint32_t)jj * 16u);
+        const float b0 = ra.x, b1 = ra.z;
+        const int t0 = __builtin_bit_cast(int, ra.y), t1 = __builtin_bit_cast(int, ra.w);
+        const float sm = __builtin_fminf(b0, b1);
+        const int c0 = (b0 == sm && t0 >= 0) ? t0 : TNONE, c1 = (b1 == sm && t1 >= 0) ? t1 : TNONE;
+        const int tm = c0 < c1 ? c0 : c1;
+        uint32_t cand = (uint32_t)(c0 == tm) | ((uint32_t)(c1 == tm) << 1);
+        if (tm == TNONE || !live) cand = 0u;
+        const uint4 g = gc8[n];
+        const uint32_t og = live ? g.z : ORIGIN_NONE;
+        const uint32_t hs = (uint32_t)((jj % SLOTS) & 1);
+        int bi = IDX_NONE;
+        while (__any(cand != 0u)) {
+            const uint32_t qe = cand ? (uint32_t)__builtin_ctz(cand) : 0u;
+            const uint32_t pA = 2u * hs + qe, pB = 2u * (1u - hs) + qe;
+            const uint32_t tb0 = cand ? (uint32_t)tm * (uint32_t)TILE_BYTES : 0xfff00000u;
+            v4f sA, sB;
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const uint32_t x = ((m < 4 ? g.x : g.y) >> (8 * (m & 3))) & 255u;
+                const uint32_t o = tb0 + (x << 6);
+                const v4f vA = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pA * 16u, m * PLANE, 0));
+                const v4f vB = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_img, o + pB * 16u, m * PLANE, 0));
+                if (m == 0) { sA = vA; sB = vB; }
+                else { sA = sA + vA; sB = sB + vB; }
+            }
+            if (cand) {
+                const int kA = tm * TK + (int)pA * 4, kB = tm * TK + (int)pB * 4;
+                int k = IDX_NONE;
+                auto take = [&](const v4f& v, int k0) {
+                    int kk = IDX_NONE;
+                    if (v.w == sm) kk = k0 + 3;
+                    if (v.z == sm) kk = k0 + 2;
+                    if (v.y == sm) kk = k0 + 1;
+                    if (v.x == sm) kk = k0;
+                    k = kk < k ? kk : k;
+                };
+                take(sA, kA); take(sB, kB);
+                bi = k < bi ? k : bi;
+                cand &= cand - 1u;
+            }
+        }
+        if (og != ORIGIN_NONE) {
+            const int kw = (bi == IDX_NONE) ? 0 : bi;
+            assign[og] = kw;
+            if (dist) dist[og] = sm;
+            if (ro.count) ro.rank[og] = atomicAdd(&ro.count[kw], 1u);
         }
     }
 }

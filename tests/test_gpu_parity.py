@@ -133,7 +133,7 @@ def test_assign_regrouped_scan(env, variant, kind, N):
         _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73, 74, 75, 76, 77, 78])
+@pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73, 74, 75, 76, 77, 78, 80, 81, 82, 83, 84])
 @pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 300007), ("uniform", 4093), ("uniform", 3),
                                     ("one_class", 5000), ("latin", 8192)])
 def test_assign_regrouped_scan_64bit_codes(env, variant, kind, N):
@@ -156,7 +156,7 @@ def test_assign_regrouped_scan_64bit_codes(env, variant, kind, N):
             codes = (codes & 0xFC) | lat
     tables = env["oracle"].build_tables(W.codewords(w))
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
-    if variant == 70:
+    if variant in (70, 80):
         ham = np.ones((8, 256, 256), np.float32)
         for m in range(8):
             np.fill_diagonal(ham[m], 0)
