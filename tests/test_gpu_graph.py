@@ -1,6 +1,8 @@
 """GPU: the calls only enqueue kernels on the caller's stream, so a caller may capture them in a HIP graph.
 
-``pqkm_fit`` (tile images, regrouping, scan, histogram, vote; no memset nodes, no allocation, no synchronisation)
+``pqkm_fit`` (tile images, regrouping or subcode words, scan, histogram path, vote; no memset nodes, no allocation, no
+synchronisation; the last three cases: the M = 4 scan with two lanes per code, the sliding-window scan of 32-byte codes and
+the regrouped M = 8 scan, each handing ranks to the sorted-path histogram)
 is captured once and replayed several times with eager work and synchronisations between the replays; every
 replay must reproduce the eager result bit for bit (the eager path itself is checked against the oracle in
 test_gpu_parity.py).
@@ -14,7 +16,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("cfg,over,iters", [(1, {}, 3), (2, dict(N=150_000, K=600), 2), (2, dict(N=600_000, K=600), 2), (3, dict(N=60_000, K=300), 2),
-                                             (3, dict(N=4_300_000, K=300), 2)])
+                                             (3, dict(N=4_300_000, K=300), 2), (2, dict(N=8_500_000, K=9_000), 2),
+                                             (4, dict(N=300_000, K=3_000), 2), (3, dict(N=4_300_000, K=9_000), 2)])
 def test_fit_replays_in_a_graph(cfg, over, iters):
     import torch
 

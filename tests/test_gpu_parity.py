@@ -701,7 +701,8 @@ def test_config2_sift32_all_iterations(env):
     _run_config_full(env, 2, workload(2).iters)
 
 
-@pytest.mark.parametrize("cfg,over", [(1, {}), (2, dict(N=200_000, K=300, T=600)), (3, dict(N=50_000, K=200, T=300))])
+@pytest.mark.parametrize("cfg,over", [(1, {}), (2, dict(N=200_000, K=300, T=600)), (3, dict(N=50_000, K=200, T=300)),
+                                      (2, dict(N=540_001, K=9_000, T=12_000))])
 def test_fit_until_matches_oracle(env, cfg, over):
     """Alg. 1 with the stop condition: same number of iterations, integer statistics exact, the fp64
     objective within 1e-9 relative (it is a sum of N fp32 terms in a different order: error <= N * 2^-53),
