@@ -36,6 +36,11 @@ extern "C" {
  *                        groups (falls back when K needs more than 255 groups), 3 = force the
  *                        histogram over code indices sorted by cluster
  *   "launch_codes_log2"  the scan is issued in launches of 2^value codes (default 26)
+ *   "scan_rounds_per_launch"  the large scans (two-lane M = 4 scan, regrouped M = 8 scan, sliding-window
+ *                        scan) issue the workgroups of such a launch in kernel launches of `value`
+ *                        rounds (one workgroup per compute unit) each, so that the workgroups start
+ *                        in step and share the tile images through the L2 (default 1); 0 = one
+ *                        kernel launch for all of them
  *   "profile"            bit 0 (value 1) = bracket every scan-kernel launch with a pair of HIP
  *                        events on the caller's stream; bit 1 (value 2) = bracket every whole
  *                        assignment step (tile images, regrouping of the codes where it is

@@ -27,6 +27,7 @@ struct Options {
     int hist_kernel = 0;     // 0 auto, 1 global atomics, 2 LDS-privatised owner path, 3 sorted by cluster
     int profile = 0;         // bit 0: bracket scan kernels with events, bit 1: bracket whole assignment steps
     int64_t launch_codes = (int64_t)1 << 26;   // codes per scan launch
+    int rounds_per_launch = 1;                 // big scans: rounds of workgroups per kernel launch, 0 = all in one
 };
 Options g_opt;
 std::mutex g_mu;
@@ -318,10 +319,21 @@ inline int variant_layout(int M, int variant)
 
 template <int R, int THREADS, int DEPTH>
 void launch_scan8p(const uint8_t* codes, int64_t N, const uint4* gc8, const float4* img, int ntiles, int32_t* assign,
-                   float* dist, hipStream_t st, RankOut ro = RankOut{})
+                   float* dist, hipStream_t st, RankOut ro = RankOut{}, int rounds_per_launch = 0)
 {
     constexpr int C = (THREADS / 4) * R;
     int64_t nwg = (N + C - 1) / C;
+    if (gc8 && rounds_per_launch > 0) {
+        // regrouped codes, results go to the codes' original positions: any stretch of workgroups can be a launch
+        // of its own, and the workgroups of a launch start in step (see launch_scan4q_rounds)
+        const int64_t per = (int64_t)rounds_per_launch * cu_count();
+        for (int64_t w0 = 0; w0 < nwg; w0 += per) {
+            const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
+            hipLaunchKernelGGL((assign_scan8p_kernel<R, THREADS, DEPTH>), dim3((unsigned)cnt), dim3(THREADS), 0, st, codes,
+                               N - w0 * C, gc8 + w0 * C, img, ntiles, assign, dist, ro);
+        }
+        return;
+    }
     hipLaunchKernelGGL((assign_scan8p_kernel<R, THREADS, DEPTH>), dim3((unsigned)nwg), dim3(THREADS), 0, st, codes, N,
                        gc8, img, ntiles, assign, dist, ro);
 }
@@ -351,7 +363,7 @@ inline int sw_codes_per_slot(int variant, int64_t n)
 
 template <int M>
 pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_t* S, const float4* img, int ntiles16,
-                           int32_t* assign, float* dist, hipStream_t st, RankOut ro = RankOut{})
+                           int32_t* assign, float* dist, hipStream_t st, RankOut ro = RankOut{}, int rounds_per_launch = 0)
 {
     const int R = sw_codes_per_slot(variant, N);
     const int64_t C = 256 * (int64_t)R;
@@ -359,15 +371,17 @@ pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_
     const int64_t n_alloc = nwg * C;
     hipLaunchKernelGGL((code_skew_kernel<M>), dim3((unsigned)((n_alloc + 255) / 256)), dim3(256), 0, st, codes, N, S,
                        n_alloc);
-    switch (R) {
-        case 8:
-            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 8, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
-                               n_alloc, img, ntiles16, assign, dist, ro);
-            break;
-        default:
-            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, codes, N, S,
-                               n_alloc, img, ntiles16, assign, dist, ro);
-            break;
+    // kernel launches of rounds_per_launch rounds of workgroups each, so that the workgroups start in step again
+    // (see launch_scan4q_rounds)
+    const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
+    for (int64_t w0 = 0; w0 < nwg; w0 += per) {
+        const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
+        if (R == 8)
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 8, 512, 3>), dim3((unsigned)cnt), dim3(512), 0, st, codes, N, S,
+                               n_alloc, img, ntiles16, assign, dist, ro, w0);
+        else
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 2>), dim3((unsigned)cnt), dim3(512), 0, st, codes, N, S,
+                               n_alloc, img, ntiles16, assign, dist, ro, w0);
     }
     return launched();
 }
@@ -454,8 +468,26 @@ int scan4q_codes_per_slot(int variant, int64_t n_alloc)
     return best;
 }
 
+template <int R>
+void launch_scan4q_rounds(const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows, int ntiles,
+                          int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+{
+    // The workgroups of a kernel launch start together and walk the tile images in step, so that a tile is fetched
+    // from memory once per XCD and then served from its L2; over many rounds of workgroups they drift apart.  With
+    // rounds_per_launch > 0 the codes are issued in kernel launches of that many rounds, each starting in step again.
+    constexpr int64_t C = 256 * (int64_t)R;
+    const int64_t nwg = (n_alloc + C - 1) / C;
+    const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
+    for (int64_t w0 = 0; w0 < nwg; w0 += per) {
+        const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
+        hipLaunchKernelGGL((assign_scan4q_kernel<R, 512, 2>), dim3((unsigned)cnt), dim3(512), 0, st, n_alloc - w0 * C,
+                           gco + w0 * C, img, rows, ntiles, assign, dist, ro, TileSource{});
+    }
+}
+
 void launch_scan_grouped_q(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
-                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro, TileSource ts)
+                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro, TileSource ts,
+                           int rounds_per_launch)
 {
     const int R = scan4q_codes_per_slot(variant >= 90 ? variant - 10 : variant, n_alloc);
     const int64_t nwg = (n_alloc + 256 * (int64_t)R - 1) / (256 * (int64_t)R);
@@ -481,23 +513,10 @@ void launch_scan_grouped_q(int variant, const uint2* gco, int64_t n_alloc, const
         return;
     }
     switch (R) {
-        case 16:
-            hipLaunchKernelGGL((assign_scan4q_kernel<16, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
-                               rows, ntiles, assign, dist, ro);
-            break;
-        case 24:
-            hipLaunchKernelGGL((assign_scan4q_kernel<24, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
-                               rows, ntiles, assign, dist, ro);
-            break;
-        case 26:
-            hipLaunchKernelGGL((assign_scan4q_kernel<26, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
-                               rows, ntiles, assign, dist, ro);
-            break;
-
-        default:
-            hipLaunchKernelGGL((assign_scan4q_kernel<28, 512, 2>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gco, img,
-                               rows, ntiles, assign, dist, ro);
-            break;
+        case 16: launch_scan4q_rounds<16>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 24: launch_scan4q_rounds<24>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 26: launch_scan4q_rounds<26>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan4q_rounds<28>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
     }
 }
 
@@ -519,14 +538,14 @@ int scan8p_codes_per_slot(int64_t n_alloc)
 }
 
 void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
-                          float* dist, hipStream_t st, RankOut ro = RankOut{})
+                          float* dist, hipStream_t st, RankOut ro = RankOut{}, int rpl = 0)
 {
     int R = 0;
     switch (variant) {
         case 70: R = scan8p_codes_per_slot(n_alloc); break;
-        case 71: launch_scan8p<12, 1024, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
-        case 72: launch_scan8p<16, 512, 8>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
-        case 73: launch_scan8p<24, 512, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); return;
+        case 71: launch_scan8p<12, 1024, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); return;
+        case 72: launch_scan8p<16, 512, 8>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); return;
+        case 73: launch_scan8p<24, 512, 2>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); return;
         case 74: R = 25; break;
         case 75: R = 22; break;
         case 76: R = 20; break;
@@ -535,12 +554,12 @@ void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const 
         default: R = 24; break;
     }
     switch (R) {
-        case 16: launch_scan8p<16, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
-        case 18: launch_scan8p<18, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
-        case 20: launch_scan8p<20, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
-        case 22: launch_scan8p<22, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
-        case 25: launch_scan8p<25, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
-        default: launch_scan8p<24, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro); break;
+        case 16: launch_scan8p<16, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
+        case 18: launch_scan8p<18, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
+        case 20: launch_scan8p<20, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
+        case 22: launch_scan8p<22, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
+        case 25: launch_scan8p<25, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
+        default: launch_scan8p<24, 512, 4>(nullptr, n_alloc, gc8, img, ntiles, assign, dist, st, ro, rpl); break;
     }
 }
 
@@ -835,7 +854,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             if constexpr (M == 16 || M == 32) {
                 if (launch_scan_sw<M>(variant, codes + n0 * M, cnt, reinterpret_cast<uint32_t*>(ws + c.skew_off),
                                       reinterpret_cast<const float4*>(img), (int)ntiles, assign + n0,
-                                      dist ? dist + n0 : nullptr, st, rl) != PQKM_OK)
+                                      dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch) != PQKM_OK)
                     return PQKM_ERR_DEVICE;
             }
         } else if (M == 8 && variant_two_lane(M, variant))
@@ -843,10 +862,10 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
                                    assign + n0, dist ? dist + n0 : nullptr, st, rl);
         else if (variant_two_lane(M, variant))
             launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
-                                  assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc);
+                                  assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc, opt.rounds_per_launch);
         else if (grouped && M == 8)
             launch_scan_grouped8(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
-                                 assign + n0, dist ? dist + n0 : nullptr, st, rl);
+                                 assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
         else if (grouped && M == 4 && link && link->wanted && variant == 70 && N <= per_launch &&
                  c.bseg_off != c.pool_off) {
             BucketOut bo{reinterpret_cast<uint2*>(ws + c.pool_off), reinterpret_cast<uint2*>(ws + c.bseg_off), link->KT,
@@ -1410,6 +1429,9 @@ pqkm_status pqkm_set_option(const char* name, int32_t value)
     } else if (strcmp(name, "profile") == 0) {
         if (value < 0 || value > 3) return PQKM_ERR_SHAPE;
         g_opt.profile = value;
+    } else if (strcmp(name, "scan_rounds_per_launch") == 0) {
+        if (value < 0 || value > 1024) return PQKM_ERR_SHAPE;
+        g_opt.rounds_per_launch = value;
     } else if (strcmp(name, "launch_codes_log2") == 0) {
         if (value < 10 || value > 40) return PQKM_ERR_SHAPE;
         g_opt.launch_codes = (int64_t)1 << value;

@@ -2369,7 +2369,8 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
                                                                  const uint32_t* __restrict__ S, int64_t n_alloc,
                                                                  const float4* __restrict__ img, int ntiles,
                                                                  int32_t* __restrict__ assign,
-                                                                 float* __restrict__ dist, RankOut ro = RankOut{})
+                                                                 float* __restrict__ dist, RankOut ro = RankOut{},
+                                                                 int64_t first_workgroup = 0)
 {
     constexpr int TK = 16, LPS = 2, NPH = M / 4 + 1;
     constexpr int SLOTS = THREADS / LPS;
@@ -2389,7 +2390,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
     const int c = tid >> 1;
     const int j = (c & 7) >> 1;                       // subspaces this slot runs behind
     const int h = c & 1;                              // 1: the lanes read the upper of their two pieces first
-    const int64_t base = (int64_t)blockIdx.x * C;
+    const int64_t base = ((int64_t)blockIdx.x + first_workgroup) * C;   // a launch may cover a stretch of the workgroups
     const uint32_t nine = 9;
 
     if (tid < 16) tile[TILE_F4 + tid] = make_float4(-0.0f, -0.0f, -0.0f, -0.0f);
