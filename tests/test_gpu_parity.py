@@ -429,6 +429,49 @@ def test_random_shapes_assign_then_update(env, seed):
         np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("seed", [31, 32, 33])
+def test_random_shapes_forced_large_input_scans(env, seed):
+    """The scans that are the default only for large inputs (two lanes per code for M = 4 and M = 8, table-built
+    tiles, the sliding-window scan for M = 16 and 32), forced on seeded random shapes and value mixes: one
+    workgroup to a few, one tile to many, ragged everything; real and integer tables; assignment and distances bit
+    for bit, then a two-iteration pqkm_fit with the same variant forced."""
+    pq, oracle = env["pq"], env["oracle"]
+    rng = np.random.default_rng(seed)
+    choices = [(4, 80), (4, 82), (4, 84), (4, 90), (4, 93), (8, 80), (8, 82), (8, 84), (16, 50), (16, 52), (32, 50), (32, 51)]
+    for case in range(12):
+        M, variant = choices[int(rng.integers(0, len(choices)))]
+        N = int(rng.integers(1, 120_000)) if M <= 8 else int(rng.integers(1, 40_000))
+        K = int(rng.integers(1, 1500))
+        kind = ("uniform", "skew", "few")[int(rng.integers(0, 3))]
+        if kind == "uniform":
+            codes = rng.integers(0, 256, (N, M), dtype=np.uint8)
+        elif kind == "skew":
+            codes = (rng.integers(0, 256, (N, M)) * rng.integers(0, 2, (N, M)) | rng.integers(0, 4, (N, 1))).astype(np.uint8)
+        else:
+            codes = rng.integers(0, 5, (N, M), dtype=np.uint8)
+        centers = codes[rng.integers(0, N, K)].copy()
+        tables = rand_tables(rng, M, integer=bool(rng.integers(0, 2)))
+        progress(f"forced-scan case seed={seed} #{case}: M={M} variant={variant} N={N} K={K} {kind}")
+        _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
+        torch = env["torch"]
+        hist = torch.empty((K, M, 256), dtype=torch.int32, device=env["dev"])
+        counts = torch.empty((K,), dtype=torch.int32, device=env["dev"])
+        d_cent = _dev(env, centers)
+        pq.set_option("assign_kernel", 2)
+        pq.set_option("scan_variant", variant)
+        try:
+            _, fa = pq.fit(_dev(env, codes), _dev(env, tables), d_cent, 2, hist=hist, counts=counts)
+            _sync(env)
+        finally:
+            pq.set_option("assign_kernel", 0)
+            pq.set_option("scan_variant", 0)
+        rc, ra, rh, rcnt = oracle.fit(codes, tables, centers, 2)
+        np.testing.assert_array_equal(fa.cpu().numpy(), ra)
+        np.testing.assert_array_equal(u32(hist), rh)
+        np.testing.assert_array_equal(u32(counts), rcnt)
+        np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_shapes_fused_iteration(env, seed):
     """Seeded random shapes above one round of 2048-code workgroups (M = 4, K >= 128), where pqkm_fit runs the
