@@ -49,8 +49,11 @@ extern "C" {
  *                        the library creates HIP objects.
  *
  * pqkm_profile_read / pqkm_profile_read_steps: wait for the recorded stop events, return the
- * summed elapsed time of the bracketed scan launches / assignment steps in milliseconds and
- * their number, and reset that record.  They block the host.
+ * summed elapsed time of the bracketed scan kernels / assignment steps in milliseconds and
+ * their number, and reset that record.  A pair of events brackets the scan kernels of one
+ * stretch of codes (one launch, or one per round of workgroups, back to back on the stream);
+ * `launches` counts the kernels, so total_ms / launches is the average duration of a scan
+ * kernel, the short gaps between consecutive launches included.  They block the host.
  *   total_ms, launches / steps   host pointers, out
  */
 pqkm_status pqkm_set_option(const char *name, int32_t value);

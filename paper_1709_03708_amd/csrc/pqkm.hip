@@ -45,8 +45,12 @@ struct EventPair { hipEvent_t a, b; };
 struct EventLog {
     std::vector<EventPair> pool;    // all events ever created
     size_t used = 0;                // pairs recorded since the last read
+    int64_t kernels = 0;            // kernel launches inside those pairs (scan log only)
 };
-EventLog g_scan_log, g_step_log;    // around every scan launch / around every whole assignment step
+EventLog g_scan_log, g_step_log;    // around the scan kernels of a stretch of codes / around every whole assignment step
+// scan kernels launched by this thread since it was last cleared: a stretch of codes is one launch, or one launch
+// per round of workgroups
+thread_local int64_t t_scan_kernels = 0;
 
 // start of a bracket: takes (or creates) a pair and records its first event; false if none could be had
 bool log_begin(EventLog& log, hipStream_t st, EventPair* ev)
@@ -76,8 +80,9 @@ pqkm_status log_read(EventLog& log, double* total_ms, int64_t* count)
         tot += ms;
     }
     *total_ms = tot;
-    *count = (int64_t)log.used;
+    *count = log.kernels ? log.kernels : (int64_t)log.used;
     log.used = 0;
+    log.kernels = 0;
     return PQKM_OK;
 }
 
@@ -331,6 +336,7 @@ void launch_scan8p(const uint8_t* codes, int64_t N, const uint4* gc8, const floa
             const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
             hipLaunchKernelGGL((assign_scan8p_kernel<R, THREADS, DEPTH>), dim3((unsigned)cnt), dim3(THREADS), 0, st, codes,
                                N - w0 * C, gc8 + w0 * C, img, ntiles, assign, dist, ro);
+            ++t_scan_kernels;
         }
         return;
     }
@@ -382,6 +388,7 @@ pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_
         else
             hipLaunchKernelGGL((assign_scan_sw_kernel<M, 16, 512, 2>), dim3((unsigned)cnt), dim3(512), 0, st, codes, N, S,
                                n_alloc, img, ntiles16, assign, dist, ro, w0);
+        ++t_scan_kernels;
     }
     return launched();
 }
@@ -482,6 +489,7 @@ void launch_scan4q_rounds(const uint2* gco, int64_t n_alloc, const float4* img, 
         const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
         hipLaunchKernelGGL((assign_scan4q_kernel<R, 512, 2>), dim3((unsigned)cnt), dim3(512), 0, st, n_alloc - w0 * C,
                            gco + w0 * C, img, rows, ntiles, assign, dist, ro, TileSource{});
+        ++t_scan_kernels;
     }
 }
 
@@ -850,6 +858,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         }
         EventPair ev{};
         const bool prof = (opt.profile & 1) && log_begin(g_scan_log, st, &ev);
+        t_scan_kernels = 0;
         if (sliding) {
             if constexpr (M == 16 || M == 32) {
                 if (launch_scan_sw<M>(variant, codes + n0 * M, cnt, reinterpret_cast<uint32_t*>(ws + c.skew_off),
@@ -879,7 +888,11 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         else
             launch_scan_M<M>(variant, codes + n0 * M, cnt, reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                              assign + n0, dist ? dist + n0 : nullptr, st);
-        if (prof) hipEventRecord(ev.b, st);
+        if (prof) {
+            hipEventRecord(ev.b, st);
+            std::lock_guard<std::mutex> lk(g_mu);
+            g_scan_log.kernels += t_scan_kernels > 0 ? t_scan_kernels : 1;
+        }
         if (launched() != PQKM_OK) return PQKM_ERR_DEVICE;
     }
     return PQKM_OK;
