@@ -528,6 +528,52 @@ void launch_scan_grouped_q(int variant, const uint2* gco, int64_t n_alloc, const
     }
 }
 
+// M = 4, two-lane slots, half tiles loaded straight into LDS (variants 85..89): codes per workgroup
+struct Scan4hShape { int R, threads; };
+Scan4hShape scan4h_shape(int variant)
+{
+    switch (variant) {
+        case 86: return {12, 1024};
+        case 87: return {14, 1024};
+        case 88: return {32, 512};
+        case 89: return {8, 1024};
+        default: return {16, 1024};
+    }
+}
+inline int64_t scan4h_codes_per_workgroup(int variant)
+{
+    const Scan4hShape sh = scan4h_shape(variant);
+    return (int64_t)(sh.threads / 2) * sh.R;
+}
+
+template <int R, int THREADS, int DEPTH>
+void launch_scan4h_rounds(const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows, int ntiles,
+                          int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+{
+    // one kernel launch per rounds_per_launch rounds of workgroups (see launch_scan4q_rounds)
+    constexpr int64_t C = (THREADS / 2) * (int64_t)R;
+    const int64_t nwg = (n_alloc + C - 1) / C;
+    const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
+    for (int64_t w0 = 0; w0 < nwg; w0 += per) {
+        const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
+        hipLaunchKernelGGL((assign_scan4h_kernel<R, THREADS, DEPTH>), dim3((unsigned)cnt), dim3(THREADS), 0, st,
+                           n_alloc - w0 * C, gco + w0 * C, img, rows, ntiles, assign, dist, ro);
+        ++t_scan_kernels;
+    }
+}
+
+void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
+                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+{
+    switch (variant) {
+        case 86: launch_scan4h_rounds<12, 1024, 4>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 87: launch_scan4h_rounds<14, 1024, 3>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 88: launch_scan4h_rounds<32, 512, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 89: launch_scan4h_rounds<8, 1024, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan4h_rounds<16, 1024, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+    }
+}
+
 // M = 8 scans over regrouped codes: variants 70..79.  Variant 70 chooses the codes per lane-slot like the M = 4
 // scan does: rounds * (R + 9) with rounds = ceil(workgroups / CUs) (8e6 codes: 11 rounds of 2605 workgroups at
 // R = 24, 10 rounds of 2500 at R = 25, measured 12.2 ms against 11.4 ms at K = 4000).
@@ -772,6 +818,7 @@ inline bool variant_two_lane(int M, int variant)
     return (M == 4 && variant >= 80 && variant <= 99) || (M == 8 && variant >= 80 && variant <= 84);
 }
 inline bool variant_table_tiles(int M, int variant) { return M == 4 && variant >= 90 && variant <= 99; }
+inline bool variant_lds_loads(int M, int variant) { return M == 4 && variant >= 85 && variant <= 89; }
 inline bool variant_sliding(int M, int variant) { return (M == 16 || M == 32) && variant >= 50 && variant <= 59; }
 
 // The fused iteration's hand-over from the scan to the histogram: filled in by the caller (wanted, KT, ngroups),
@@ -792,11 +839,11 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
     int variant = effective_variant(M, opt.scan_variant, N, K, codes);
-    // Many rounds of workgroups and no records to file for the histogram: the scan with two-lane slots, whose
-    // workgroups take twice the codes per tile fill
+    // Many rounds of workgroups and no records to file for the histogram: the scan with two-lane slots whose tiles
+    // are loaded straight into LDS, half a tile ahead
     if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 23) &&
         !(link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off))
-        variant = 80;
+        variant = 85;
     const int layout = variant_layout(M, variant);
     const bool sliding = variant_sliding(M, variant);
     if (sliding) {
@@ -820,6 +867,11 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     // a little below the limit: with its padding a launch of exactly 2^26 codes needs one workgroup more than
     // 64 full rounds of 4096-code workgroups, and that workgroup would run a round of its own
     if ((grouped || sliding) && per_launch > GROUP_CHUNK_MAX - 16384) per_launch = GROUP_CHUNK_MAX - 16384;
+    if (variant_lds_loads(M, variant)) {
+        // whole rounds of these large workgroups per stretch (the regrouped copy pads a stretch by less than 32 codes)
+        const int64_t round = (int64_t)cu_count() * scan4h_codes_per_workgroup(variant);
+        if (per_launch >= round) per_launch = per_launch / round * round - 32;
+    }
     const float4* rows = reinterpret_cast<const float4*>(ws + c.rows_off);
     uint2* gco = reinterpret_cast<uint2*>(ws + c.gco_off);
     GroupPlan* plan = reinterpret_cast<GroupPlan*>(ws + c.plan_off);
@@ -869,6 +921,9 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         } else if (M == 8 && variant_two_lane(M, variant))
             launch_scan_grouped8_q(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                    assign + n0, dist ? dist + n0 : nullptr, st, rl);
+        else if (variant_lds_loads(M, variant))
+            launch_scan_grouped_h(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
+                                  assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
         else if (variant_two_lane(M, variant))
             launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc, opt.rounds_per_launch);

@@ -1517,6 +1517,238 @@ __global__ __launch_bounds__(THREADS) void assign_scan4q_kernel(int64_t N, const
 }
 
 // ---------------------------------------------------------------------------------------------
+// M = 4 scan with two-lane slots whose tiles arrive in LDS without passing through registers.
+//
+// Same regrouped codes, same tile image (img[tile][m][h][x][16 centers]), same packed offsets and the same sums as
+// assign_scan4q_kernel.  What differs is how a tile gets into LDS.  There the next tile waits in 64 registers per
+// lane and is written between two barriers, while no wave can read; here the two halves of a tile (h = 0: its
+// first 16 centers, h = 1: the other 16; 64 KB each, the planes [m][h] of both interleaved exactly as in the image)
+// are two buffers: while the workgroup scans one half, buffer loads with the LDS as their destination bring the
+// half after it into the other one, 16 bytes per lane and 1 KB per wave and instruction, and a wave waits for its
+// own loads only at the one barrier per half.  The registers that held the prefetch hold more codes instead (a
+// 64 KB fill is shared by 256 R codes with R up to 48), and the LDS never idles for a fill.  The price: a code
+// passes over its tile twice (once per half), so a step is two 16-byte reads instead of four for the same unpack
+// and xor.  Per code and lane: two registers of packed row offsets, the running minimum, the HALF tile
+// (2 tile + h) in which it last improved.
+// ---------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from a buffer straight into LDS: lane l of the wave writes LDS bytes lds_addr + 16 l .. + 15
+// (lds_addr is the same for the whole wave) with the 16 bytes at buffer offset voffset + soffset.  Counted like
+// any other vector memory load (s_waitcnt vmcnt).
+__device__ __forceinline__ void buffer_to_lds16(uint32_t lds_addr, v4i rsrc, uint32_t voffset, uint32_t soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void wait_vector_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int R, int THREADS, int DEPTH>
+__global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const uint2* __restrict__ gco,
+                                                            const float4* __restrict__ img,
+                                                            const float4* __restrict__ rows, int ntiles,
+                                                            int32_t* __restrict__ assign, float* __restrict__ dist,
+                                                            RankOut ro)
+{
+    constexpr int LPS = 2, TK = 32;
+    constexpr int SLOTS = THREADS / LPS;
+    constexpr int C = SLOTS * R;
+    constexpr uint32_t HPLANE = 16384;      // bytes per (m, h) plane: 256 subcodes x 16 centers
+    static_assert(R % 2 == 0, "the epilogue gives every lane R / 2 codes");
+    static_assert(C * 8 <= TILE_BYTES, "one 8-byte record per code must fit the tile buffer");
+
+    __shared__ float4 tile[TILE_F4];
+    const char* tb = reinterpret_cast<const char*>(tile);
+
+    const int tid = threadIdx.x;
+    const int q = tid & 1;
+    const int c = tid >> 1;
+    const uint32_t hq = ((uint32_t)(c & 1) << 5) | ((uint32_t)q << 4);    // the slot's first half of the row, the lane's piece
+    const int64_t base = (int64_t)blockIdx.x * C;
+    const uint32_t low15 = 0x7fffu;
+
+    // the whole image as one buffer; the workgroup brings in a half (t, h) in NCH chunks of 16 bytes per lane
+    constexpr uint32_t CHUNK = THREADS * 16;
+    constexpr int NCH = 4 * HPLANE / CHUNK;
+    static_assert(HPLANE % CHUNK == 0 || CHUNK % HPLANE == 0, "a chunk is a whole plane or a whole fraction of one");
+    const uint64_t ip = reinterpret_cast<uint64_t>(img);
+    const v4i rs_img = {(int)(uint32_t)ip, (int)(uint32_t)(ip >> 32), (int)((uint32_t)ntiles * (uint32_t)TILE_BYTES),
+                        0x00020000};
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)tile;    // LDS byte address of the buffer
+    const uint32_t wave_off = (uint32_t)__builtin_amdgcn_readfirstlane(tid >> 6) * 1024u;
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    auto fetch = [&](int t, int h, int j) {
+        const uint32_t in_half = (uint32_t)j * CHUNK;                // plane m = in_half / HPLANE of the half
+        const uint32_t in_tile = (in_half / HPLANE) * (2 * HPLANE) + (uint32_t)h * HPLANE + in_half % HPLANE;
+        buffer_to_lds16(lds0 + in_tile + wave_off, rs_img, lane_off, (uint32_t)t * (uint32_t)TILE_BYTES + in_tile);
+    };
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) fetch(0, 0, j);
+
+    uint32_t pa[R], pb[R];
+    float best[R];
+    int tix[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t n = base + (int64_t)r * SLOTS + c;
+        if (n >= N) n = N - 1;
+        const uint32_t pk = gco[n].x;
+        const uint32_t f0 = ((pk & 255u) << 6) | hq;
+        const uint32_t f1 = (((pk >> 8) & 255u) << 6) | hq;
+        const uint32_t f2 = ((((pk >> 16) & 255u) << 6) | hq) + 65536u;
+        const uint32_t f3 = (((pk >> 24) << 6) | hq) + 65536u;
+        pa[r] = f0 | (f2 << 15);
+        pb[r] = f1 | (f3 << 15);
+        best[r] = INFINITY;
+        tix[r] = -1;
+    }
+
+    // a step is one subspace of one code in one half: two 16-byte reads (the lane's piece of either half of the row)
+    struct Pair { float4 a, b; };
+
+    for (int t = 0; t < ntiles; ++t) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // this half has arrived (own loads, then everybody's), and nobody reads the other buffer any more
+            wait_vector_loads();
+            __syncthreads();
+            const int tf = h ? t + 1 : t, hf = h ^ 1;                // the half after this one
+            const bool more = tf < ntiles;
+            auto issue = [&](int step) -> Pair {
+                const int r = step / 4, m = step % 4;
+                const uint32_t ad = (m == 0) ? unpack_low15(low15, pa[r])
+                                  : (m == 1) ? unpack_low15(low15, pb[r])
+                                  : (m == 2) ? unpack_high17(pa[r])
+                                             : unpack_high17(pb[r]);
+                const uint32_t po = ((m & 1) ? 2 * HPLANE : 0) + h * HPLANE;
+                Pair p;
+                p.a = lds_read16(tb, ad + po);
+                p.b = lds_read16(tb, (ad ^ 32u) + po);
+                return p;
+            };
+            Pair ring[DEPTH];
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) ring[d] = issue(d);
+            float4 sa, sb;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                // the chunks of the next half, spread over the first half of the codes
+#pragma unroll
+                for (int j = 0; j < NCH; ++j)
+                    if ((j * R) / (2 * NCH) == r && more) fetch(tf, hf, j);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int step = 4 * r + m;
+                    const Pair cur = ring[step % DEPTH];
+                    if (step + DEPTH < 4 * R) ring[step % DEPTH] = issue(step + DEPTH);
+                    if (m == 0) {
+                        sa = cur.a; sb = cur.b;
+                    } else {
+                        sa.x = sa.x + cur.a.x; sa.y = sa.y + cur.a.y; sa.z = sa.z + cur.a.z; sa.w = sa.w + cur.a.w;
+                        sb.x = sb.x + cur.b.x; sb.y = sb.y + cur.b.y; sb.z = sb.z + cur.b.z; sb.w = sb.w + cur.b.w;
+                    }
+                    if (m == 3) {
+                        float m8 = min3_f32(sa.x, sa.y, sa.z);
+                        m8 = min3_f32(m8, sa.w, sb.x);
+                        m8 = min3_f32(m8, sb.y, sb.z);
+                        const float nb = min3_f32(m8, sb.w, best[r]);
+                        tix[r] = (nb < best[r]) ? 2 * t + h : tix[r];
+                        best[r] = nb;
+                    }
+                }
+            }
+        }
+    }
+
+    // Epilogue.  The two lanes of a slot merge what they hold (the neighbour's minimum and half tile through a lane
+    // permutation): slot minimum, the lowest half tile among the lanes that attain it, and which lane positions do so
+    // there; one of them leaves that as the code's 8-byte record in LDS.  Then lane l finishes the codes l, l + THREADS,
+    // ...: for every lane position named by the record the 8 sums of its centers in that half are rebuilt from the
+    // row-ordered copy of the images ([tile][m][x][32 centers]: same bits, same order of additions) and the lowest
+    // center index with that sum is kept.
+    constexpr int CPL = R / 2;
+    constexpr int TNONE = 0x7fffffff;
+    __syncthreads();
+    {
+        uint2* rec = reinterpret_cast<uint2*>(tile);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float ob = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, best[r]), 0xB1, 0xf, 0xf, true));
+            const int ot = __builtin_amdgcn_update_dpp(0, tix[r], 0xB1, 0xf, 0xf, true);      // lanes 2 i and 2 i + 1 swapped
+            const float sm = __builtin_fminf(best[r], ob);
+            const int cm = (best[r] == sm && tix[r] >= 0) ? tix[r] : TNONE, co = (ob == sm && ot >= 0) ? ot : TNONE;
+            const int um = cm < co ? cm : co;
+            const uint32_t mine = (uint32_t)(cm == um), other = (uint32_t)(co == um);
+            const uint32_t cand = (um == TNONE) ? 0u : (q ? (other | (mine << 1)) : (mine | (other << 1)));
+            if (q == (r & 1))
+                rec[r * SLOTS + c] = make_uint2(__builtin_bit_cast(uint32_t, sm), (um == TNONE ? 0u : (uint32_t)um) | (cand << 30));
+        }
+    }
+    __syncthreads();
+    __amdgpu_buffer_rsrc_t rs_rows = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float4*>(rows), 0, (uint32_t)ntiles * (uint32_t)TILE_BYTES, 0x00020000);
+#pragma unroll 1
+    for (int i0 = 0; i0 < CPL; ++i0) {
+        const int jj = i0 * THREADS + tid;           // code index in the workgroup: slot jj % SLOTS, round jj / SLOTS
+        int64_t n = base + jj;
+        const bool live = n < N;
+        if (!live) n = N - 1;
+        const uint2 rc = reinterpret_cast<const uint2*>(tile)[jj];
+        const float sm = __builtin_bit_cast(float, rc.x);
+        const int um = (int)(rc.y & 0x3fffffffu);
+        uint32_t cand = live ? (rc.y >> 30) : 0u;
+        const int tm = um >> 1;
+        const uint32_t h = (uint32_t)(um & 1);
+        const uint2 g = gco[n];
+        const uint32_t pk = g.x;
+        const uint32_t og = live ? g.y : ORIGIN_NONE;
+        const uint32_t hs = (uint32_t)(jj & 1);      // which half of the row the code's slot read first
+        int bi = IDX_NONE;
+        while (__any(cand != 0u)) {                  // one trip unless the two lane positions tie exactly
+            const uint32_t qe = cand ? (uint32_t)__builtin_ctz(cand) : 0u;
+            // lane position qe of a slot with first half hs owns the pieces 2 hs + qe (first read) and 2 (1 - hs) + qe
+            const uint32_t pA = 2u * hs + qe, pB = 2u * (1u - hs) + qe;
+            const uint32_t tb0 = cand ? (uint32_t)tm * (uint32_t)TILE_BYTES + h * 64u : 0xfff00000u;
+            v4f sA, sB;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t x = (pk >> (8 * m)) & 255u;
+                const uint32_t o = tb0 + (x << 7);
+                constexpr int MP = 32768;             // bytes per subspace in a tile of the row copy
+                const v4f vA = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_rows, o + pA * 16u, m * MP, 0));
+                const v4f vB = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs_rows, o + pB * 16u, m * MP, 0));
+                if (m == 0) { sA = vA; sB = vB; }
+                else { sA = sA + vA; sB = sB + vB; }
+            }
+            if (cand) {
+                const int kt = tm * TK + 16 * (int)h;
+                const int kA = kt + (int)pA * 4, kB = kt + (int)pB * 4;
+                int k = IDX_NONE;
+                auto take = [&](const v4f& v, int k0) {
+                    int kk = IDX_NONE;
+                    if (v.w == sm) kk = k0 + 3;
+                    if (v.z == sm) kk = k0 + 2;
+                    if (v.y == sm) kk = k0 + 1;
+                    if (v.x == sm) kk = k0;
+                    k = kk < k ? kk : k;
+                };
+                take(sA, kA); take(sB, kB);
+                bi = k < bi ? k : bi;
+                cand &= cand - 1u;
+            }
+        }
+        if (og != ORIGIN_NONE) {
+            const int kw = (bi == IDX_NONE) ? 0 : bi;
+            assign[og] = kw;
+            if (dist) dist[og] = sm;
+            if (ro.count) ro.rank[og] = atomicAdd(&ro.count[kw], 1u);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Eq. 7 from the records the scan filed by cluster group (M = 4): workgroup (g, s) owns group g
 // (KT clusters, private histograms in LDS as in the owner path) and the scan workgroups
 // w = s, s + S, ...; each of its waves takes some of them, reads group g's stretch of their

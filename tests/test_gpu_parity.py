@@ -99,7 +99,7 @@ def test_assign_every_compiled_shape(env, variant):
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
 
 
-@pytest.mark.parametrize("variant", [70, 71, 72, 73, 74, 75, 76, 80, 81, 82, 83, 84, 90, 91, 92, 93, 94])
+@pytest.mark.parametrize("variant", [70, 71, 72, 73, 74, 75, 76, 80, 81, 82, 83, 84, 85, 86, 87, 88, 89, 90, 91, 92, 93, 94])
 @pytest.mark.parametrize("kind,N", [("templates", 9001), ("uniform", 200003), ("uniform", 4093), ("uniform", 7),
                                     ("uniform", 1), ("one_class", 5000), ("two_classes", 6001), ("latin", 8192)])
 def test_assign_regrouped_scan(env, variant, kind, N):
@@ -125,12 +125,19 @@ def test_assign_regrouped_scan(env, variant, kind, N):
             codes = (codes & 0xFC) | lat
     tables = env["oracle"].build_tables(W.codewords(w))
     _check_assign(env, codes, centers, tables, assign_kernel=2, scan_variant=variant)
-    if variant in (70, 80, 90):
+    if variant in (70, 80, 85, 90):
         ham = np.ones((4, 256, 256), np.float32)
         for m in range(4):
             np.fill_diagonal(ham[m], 0)
         small = (codes % 3).astype(np.uint8)
         _check_assign(env, small, (centers % 3).astype(np.uint8), ham, assign_kernel=2, scan_variant=variant)
+        bad = rand_tables(rng, 4)                       # non-symmetric, with NaN and infinite entries
+        flat = bad.reshape(-1)
+        idx = rng.choice(flat.size, flat.size // 20, replace=False)
+        flat[idx[0::3]] = np.nan
+        flat[idx[1::3]] = np.inf
+        flat[idx[2::3]] = -np.inf
+        _check_assign(env, codes, centers, bad, assign_kernel=2, scan_variant=variant)
 
 
 @pytest.mark.parametrize("variant", [40, 41, 70, 71, 72, 73, 74, 75, 76, 77, 78, 80, 81, 82, 83, 84])
@@ -437,7 +444,7 @@ def test_random_shapes_forced_large_input_scans(env, seed):
     for bit, then a two-iteration pqkm_fit with the same variant forced."""
     pq, oracle = env["pq"], env["oracle"]
     rng = np.random.default_rng(seed)
-    choices = [(4, 80), (4, 82), (4, 84), (4, 90), (4, 93), (8, 80), (8, 82), (8, 84), (16, 50), (16, 52), (32, 50), (32, 51)]
+    choices = [(4, 80), (4, 82), (4, 84), (4, 85), (4, 86), (4, 88), (4, 89), (4, 90), (4, 93), (8, 80), (8, 82), (8, 84), (16, 50), (16, 52), (32, 50), (32, 51)]
     for case in range(12):
         M, variant = choices[int(rng.integers(0, len(choices)))]
         N = int(rng.integers(1, 120_000)) if M <= 8 else int(rng.integers(1, 40_000))
