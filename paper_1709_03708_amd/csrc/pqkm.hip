@@ -349,20 +349,26 @@ void launch_scan_M(int variant, const uint8_t* codes, int64_t N, const float4* i
                    int32_t* assign, float* dist, hipStream_t st);
 
 // Sliding-window scan of the wide codes (variants 50..59): the subcode words of this launch, then the scan.
-// R codes per lane-slot (a workgroup takes 256 R codes); variant 50 chooses R from the number of rounds:
-// a launch costs about rounds * (R + 5.5) (R codes' reads per phase, a 64 KB fill worth 4 and two barriers).
-inline int sw_codes_per_slot(int variant, int64_t n)
+// Shapes: 512 threads with 16 or 8 codes per lane-slot (4096 or 2048 codes per workgroup, variants 51 and 52) and
+// 1024 threads with 6 (3072 codes, variant 53); variant 50 chooses by the number of rounds: a round costs about
+// R + 5.5 with 512 threads (R codes' reads per phase, a 64 KB fill worth 4 and two barriers) and, measured, 0.73 of
+// the 16-code round with 1024 threads (16.3 ms against 11.9 ms per round at M = 32, K = 1e4).
+struct SwShape { int R, threads; };
+inline SwShape sw_shape(int variant, int64_t n)
 {
-    if (variant == 51) return 16;
-    if (variant == 52) return 8;
+    if (variant == 51) return {16, 512};
+    if (variant == 52) return {8, 512};
+    if (variant == 53) return {6, 1024};
     const int ncu = cu_count();
-    static const int cand[] = {16, 8};
-    int best = 16;
+    static const SwShape cand[] = {{16, 512}, {6, 1024}, {8, 512}};
+    static const double round_cost[] = {21.5, 15.7, 13.5};
+    SwShape best = cand[0];
     double best_cost = 1e300;
-    for (int R : cand) {
-        const int64_t wgs = (n + 256 * R - 1) / (256 * R);
-        const double cost = (double)((wgs + ncu - 1) / ncu) * (R + 5.5);
-        if (cost < best_cost) { best_cost = cost; best = R; }
+    for (int i = 0; i < 3; ++i) {
+        const int64_t C = (int64_t)(cand[i].threads / 2) * cand[i].R;
+        const int64_t wgs = (n + C - 1) / C;
+        const double cost = (double)((wgs + ncu - 1) / ncu) * round_cost[i];
+        if (cost < best_cost) { best_cost = cost; best = cand[i]; }
     }
     return best;
 }
@@ -371,8 +377,10 @@ template <int M>
 pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_t* S, const float4* img, int ntiles16,
                            int32_t* assign, float* dist, hipStream_t st, RankOut ro = RankOut{}, int rounds_per_launch = 0)
 {
-    const int R = sw_codes_per_slot(variant, N);
-    const int64_t C = 256 * (int64_t)R;
+    const SwShape sh = sw_shape(variant, N);
+    const bool wide = sh.threads == 1024;
+    const int R = sh.R;
+    const int64_t C = (int64_t)(sh.threads / 2) * R;
     const int64_t nwg = (N + C - 1) / C;
     const int64_t n_alloc = nwg * C;
     hipLaunchKernelGGL((code_skew_kernel<M>), dim3((unsigned)((n_alloc + 255) / 256)), dim3(256), 0, st, codes, N, S,
@@ -382,7 +390,10 @@ pqkm_status launch_scan_sw(int variant, const uint8_t* codes, int64_t N, uint32_
     const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
     for (int64_t w0 = 0; w0 < nwg; w0 += per) {
         const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
-        if (R == 8)
+        if (wide)
+            hipLaunchKernelGGL((assign_scan_sw_kernel<M, 6, 1024, 2>), dim3((unsigned)cnt), dim3(1024), 0, st, codes, N, S,
+                               n_alloc, img, ntiles16, assign, dist, ro, w0);
+        else if (R == 8)
             hipLaunchKernelGGL((assign_scan_sw_kernel<M, 8, 512, 3>), dim3((unsigned)cnt), dim3(512), 0, st, codes, N, S,
                                n_alloc, img, ntiles16, assign, dist, ro, w0);
         else

@@ -2611,7 +2611,8 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
     constexpr int NF = 4 * PLANE_F4 / THREADS;        // float4 per thread per fill (four planes)
     constexpr int SD = R;                             // the words of a whole phase are loaded one phase ahead
     constexpr uint32_t PAD = TILE_BYTES;              // 256 bytes of -0.0 after the ring
-    static_assert(THREADS == 512, "the fill mapping assumes 512 threads");
+    constexpr int XR = THREADS / 16;                  // subcode rows one float4 per thread covers in a fill
+    static_assert(THREADS == 512 || THREADS == 1024, "the fill mapping takes whole rows of 16 threads");
     static_assert(C % 8 == 0 && R % SD == 0, "slot classes repeat every 8 positions; the word ring holds SD codes");
 
     __shared__ float4 tile[TILE_F4 + 16];
@@ -2654,7 +2655,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
     auto gload = [&](int64_t plane0, int i) -> v4f {
         __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float4*>(img + (size_t)plane0 * PLANE_F4), 0, 4 * PLANE_F4 * 16, 0x00020000);
-        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, glb_r, i * 2048, 0));
+        return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rs, glb_r, i * XR * 64, 0));
     };
     v4f pf[NF];
 #pragma unroll
@@ -2662,7 +2663,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan_sw_kernel(const uint8_t* 
     auto fill = [&](int half) {
         char* dst = reinterpret_cast<char*>(tile) + lds_w + (uint32_t)half * 256u;
 #pragma unroll
-        for (int i = 0; i < NF; ++i) *reinterpret_cast<v4f*>(dst + i * 16384) = pf[i];
+        for (int i = 0; i < NF; ++i) *reinterpret_cast<v4f*>(dst + i * XR * 512) = pf[i];
     };
 
     // subcode words: S[phase][base + r*SLOTS + c], read through a buffer descriptor of the workgroup's stretch of

@@ -202,7 +202,7 @@ def test_regrouped_scan_in_several_launches(env):
 @pytest.mark.parametrize("M,variant", [(8, 0), (8, 1), (8, 2), (8, 3), (8, 4), (8, 5), (8, 6), (8, 7), (8, 10),
                                        (16, 0), (16, 1), (16, 2), (16, 3), (16, 4), (16, 6), (16, 7), (16, 10),
                                        (32, 0), (32, 1), (32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 10),
-                                       (16, 50), (16, 51), (16, 52), (32, 50), (32, 51), (32, 52)])
+                                       (16, 50), (16, 51), (16, 52), (16, 53), (32, 50), (32, 51), (32, 52), (32, 53)])
 def test_assign_every_compiled_shape_wide_codes(env, M, variant):
     w = workload(1, M=M, D=16 * M, N=7001, K=77, T=40)
     W = env["W"]
@@ -215,7 +215,7 @@ def test_assign_every_compiled_shape_wide_codes(env, M, variant):
 
 
 @pytest.mark.parametrize("M", [16, 32])
-@pytest.mark.parametrize("variant", [51, 52])
+@pytest.mark.parametrize("variant", [51, 52, 53])
 @pytest.mark.parametrize("N,K", [(1, 1), (9001, 16), (4097, 1000), (300_007, 333)])
 def test_assign_sliding_window_scan(env, M, variant, N, K):
     """The sliding-window scan of the wide codes (16 centers per tile, planes passing through a ring in the LDS,
@@ -444,7 +444,7 @@ def test_random_shapes_forced_large_input_scans(env, seed):
     for bit, then a two-iteration pqkm_fit with the same variant forced."""
     pq, oracle = env["pq"], env["oracle"]
     rng = np.random.default_rng(seed)
-    choices = [(4, 80), (4, 82), (4, 84), (4, 85), (4, 86), (4, 88), (4, 89), (4, 90), (4, 93), (8, 80), (8, 82), (8, 84), (16, 50), (16, 52), (32, 50), (32, 51)]
+    choices = [(4, 80), (4, 82), (4, 84), (4, 85), (4, 86), (4, 88), (4, 89), (4, 90), (4, 93), (8, 80), (8, 82), (8, 84), (16, 50), (16, 52), (16, 53), (32, 50), (32, 51), (32, 53)]
     for case in range(12):
         M, variant = choices[int(rng.integers(0, len(choices)))]
         N = int(rng.integers(1, 120_000)) if M <= 8 else int(rng.integers(1, 40_000))
