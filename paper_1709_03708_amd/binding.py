@@ -26,6 +26,10 @@ def load():
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        # The kernels run on torch's stream with torch's device pointers, so one HIP runtime has to serve both.
+        # torch ships its own copy of the runtime: imported first it is the one this library binds to; loaded the
+        # other way round the process holds two runtimes and every launch of this library fails.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(_LIB_PATH)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
         lib.pqkm_status_string.restype = ctypes.c_char_p

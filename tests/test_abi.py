@@ -116,6 +116,7 @@ def test_microbenchmark_library_loads_and_rejects_bad_arguments():
 
     if not os.path.exists(build.MICROBENCH_LIB):
         build.build()
+    import torch  # noqa: F401  (its HIP runtime first, as in the binding: a process must not end up with two)
     mb = ctypes.CDLL(build.MICROBENCH_LIB)
     mb.pqkm_microbench.restype = ctypes.c_int
     mb.pqkm_microbench.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]

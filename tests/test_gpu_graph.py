@@ -1,7 +1,7 @@
 """GPU: the calls only enqueue kernels on the caller's stream, so a caller may capture them in a HIP graph.
 
 ``pqkm_fit`` (tile images, regrouping or subcode words, scan, histogram path, vote; no memset nodes, no allocation, no
-synchronisation; the last three cases: the M = 4 scan with two lanes per code, the sliding-window scan of 32-byte codes and
+synchronisation; the last three cases: the M = 4 scan that loads its half tiles straight into LDS, the sliding-window scan of 32-byte codes and
 the regrouped M = 8 scan, each handing ranks to the sorted-path histogram)
 is captured once and replayed several times with eager work and synchronisations between the replays; every
 replay must reproduce the eager result bit for bit (the eager path itself is checked against the oracle in
