@@ -585,6 +585,27 @@ void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const
     }
 }
 
+// M = 4, many codes: the four-lane scan (variant 70) or one of the shapes of the LDS-direct scan (85..87), by the time
+// the rounds of workgroups take.  Clocks per tile and workgroup of C codes, from the measured times: four lanes per
+// code 2.30 C + 2065 (the fill of 128 KB between two barriers), LDS-direct 2.53 C + 1064 (two halves).
+int choose_scan4_large(int64_t n)
+{
+    const int ncu = cu_count();
+    const int64_t na = group_alloc(n);
+    auto rounds = [&](int64_t C) { return ((na + C - 1) / C + ncu - 1) / ncu; };
+    const int64_t c4p = 128 * (int64_t)scan4p_codes_per_slot(na);
+    double best_cost = (double)rounds(c4p) * (2.30 * (double)c4p + 2065.0);
+    int best = 70;
+    if (n >= ((int64_t)1 << 23)) return 85;            // stretches are cut to whole rounds of the largest shape
+    static const int cand[] = {85, 87, 86};
+    for (int v : cand) {
+        const int64_t C = scan4h_codes_per_workgroup(v);
+        const double cost = (double)rounds(C) * (2.53 * (double)C + 1064.0);
+        if (cost < best_cost) { best_cost = cost; best = v; }
+    }
+    return best;
+}
+
 // M = 8 scans over regrouped codes: variants 70..79.  Variant 70 chooses the codes per lane-slot like the M = 4
 // scan does: rounds * (R + 9) with rounds = ceil(workgroups / CUs) (8e6 codes: 11 rounds of 2605 workgroups at
 // R = 24, 10 rounds of 2500 at R = 25, measured 12.2 ms against 11.4 ms at K = 4000).
@@ -850,11 +871,11 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
     int variant = effective_variant(M, opt.scan_variant, N, K, codes);
-    // Many rounds of workgroups and no records to file for the histogram: the scan with two-lane slots whose tiles
-    // are loaded straight into LDS, half a tile ahead
-    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 23) &&
+    // No records to file for the histogram: from a few rounds of workgroups on, the scan with two-lane slots whose
+    // tiles are loaded straight into LDS, half a tile ahead, in the shape that the rounds favour
+    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 21) &&
         !(link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off))
-        variant = 85;
+        variant = choose_scan4_large(N);
     const int layout = variant_layout(M, variant);
     const bool sliding = variant_sliding(M, variant);
     if (sliding) {

@@ -716,12 +716,13 @@ def test_fit_files_codes_by_cluster_group(env, N, K, kind):
 
 
 @pytest.mark.parametrize("M,N,K", [(4, 600_007, 20_000), (8, 4_300_003, 10_000), (32, 300_007, 3_000), (16, 420_001, 5_000),
-                                   (4, 70_001, 20_000)])
+                                   (4, 70_001, 20_000), (4, 2_400_003, 20_000)])
 def test_fit_hands_ranks_to_the_sorted_histogram(env, M, N, K):
     """pqkm_fit at sizes where the histogram sorts the code indices by cluster (more than 255 cluster groups): the
     regrouped scans (4- and 8-byte codes) and the sliding-window scan (16, 32 bytes) count the clusters in their
     epilogue and leave every code's rank, so the update needs no counting pass and no atomics in its scatter.  The
-    last case takes a scan without that hand-over through the same call.  Two iterations against the oracle's loop:
+    fifth case takes a scan without that hand-over through the same call, the last one the scan that loads its half
+    tiles straight into LDS, in the shape chosen for a few rounds of workgroups.  Two iterations against the oracle's loop:
     centers, assignments, histograms, counts."""
     pq, oracle, W, torch = env["pq"], env["oracle"], env["W"], env["torch"]
     w = workload(2 if M == 4 else 3, N=N, K=K, M=M, D=16 * M)
