@@ -649,9 +649,61 @@ void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const 
     }
 }
 
+// Codes per lane-slot of the two-lane M = 8 scan (a workgroup takes 256 R codes) by the rounds, in the unit of
+// scan8p_codes_per_slot (128 codes' reads per tile): 2 R + 13.  24 codes per lane-slot spill (9 registers) and are
+// 8 % slower per code: only when forced.
+int scan8q_codes_per_slot(int64_t n_alloc, int64_t* cost_out)
+{
+    const int ncu = cu_count();
+    static const int cand[] = {22, 20, 16};
+    int best = 22;
+    int64_t best_cost = INT64_MAX;
+    for (int r : cand) {
+        const int64_t wgs = (n_alloc + 256 * r - 1) / (256 * r);
+        const int64_t cost = ((wgs + ncu - 1) / ncu) * (2 * r + 13);
+        if (cost < best_cost) { best_cost = cost; best = r; }
+    }
+    if (cost_out) *cost_out = best_cost;
+    return best;
+}
+
+// M = 8, many codes: four lanes per code (variant 70) or two (80), by the time the rounds take.  Per unit the
+// two-lane scan is about 3 % slower (the left-over groups' conflicts), and with few tiles its longer epilogue shows.
+int choose_scan8_large(int64_t n, int K)
+{
+    if (K < 512) return 70;
+    const int64_t na = group_alloc(n < GROUP_CHUNK_MAX - 16384 ? n : GROUP_CHUNK_MAX - 16384);
+    const int ncu = cu_count();
+    const int R = scan8p_codes_per_slot(na);
+    const int64_t wgs = (na + 128 * R - 1) / (128 * R);
+    const int64_t cost_p = ((wgs + ncu - 1) / ncu) * (R + 9);
+    int64_t cost_q = 0;
+    scan8q_codes_per_slot(na, &cost_q);
+    return (double)cost_q * 1.03 < (double)cost_p ? 80 : 70;
+}
+
 // M = 8 scan over regrouped codes with two-lane slots (256 R codes per workgroup): variants 80..84
+template <int R>
+void launch_scan8q_rounds(const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
+                          float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+{
+    // one kernel launch per rounds_per_launch rounds of workgroups (see launch_scan4q_rounds), 0 = one for all.
+    // The caller passes 0: measured at N = 1e7, K = 1e4, a launch per round is 4 % slower for this scan (0.606
+    // against 0.631 of the LDS peak): every round then waits for its slowest workgroup, and the conflicts of the
+    // left-over groups make the workgroups of this scan uneven.
+    constexpr int64_t C = 256 * (int64_t)R;
+    const int64_t nwg = (n_alloc + C - 1) / C;
+    const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
+    for (int64_t w0 = 0; w0 < nwg; w0 += per) {
+        const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
+        hipLaunchKernelGGL((assign_scan8q_kernel<R, 512, 3>), dim3((unsigned)cnt), dim3(512), 0, st, n_alloc - w0 * C,
+                           gc8 + w0 * C, img, ntiles, assign, dist, ro);
+        ++t_scan_kernels;
+    }
+}
+
 void launch_scan_grouped8_q(int variant, const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles,
-                            int32_t* assign, float* dist, hipStream_t st, RankOut ro)
+                            int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
 {
     int R = 0;
     switch (variant) {
@@ -659,35 +711,13 @@ void launch_scan_grouped8_q(int variant, const uint4* gc8, int64_t n_alloc, cons
         case 82: R = 22; break;
         case 83: R = 20; break;
         case 84: R = 16; break;
-        default: {
-            const int ncu = cu_count();
-            static const int cand[] = {24, 22, 20, 16};
-            int64_t best_cost = INT64_MAX;
-            for (int r : cand) {
-                const int64_t wgs = (n_alloc + 256 * r - 1) / (256 * r);
-                const int64_t cost = ((wgs + ncu - 1) / ncu) * (2 * r + 13);
-                if (cost < best_cost) { best_cost = cost; R = r; }
-            }
-        }
+        default: R = scan8q_codes_per_slot(n_alloc, nullptr); break;
     }
-    const int64_t nwg = (n_alloc + 256 * (int64_t)R - 1) / (256 * (int64_t)R);
     switch (R) {
-        case 16:
-            hipLaunchKernelGGL((assign_scan8q_kernel<16, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
-                               ntiles, assign, dist, ro);
-            break;
-        case 20:
-            hipLaunchKernelGGL((assign_scan8q_kernel<20, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
-                               ntiles, assign, dist, ro);
-            break;
-        case 22:
-            hipLaunchKernelGGL((assign_scan8q_kernel<22, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
-                               ntiles, assign, dist, ro);
-            break;
-        default:
-            hipLaunchKernelGGL((assign_scan8q_kernel<24, 512, 3>), dim3((unsigned)nwg), dim3(512), 0, st, n_alloc, gc8, img,
-                               ntiles, assign, dist, ro);
-            break;
+        case 16: launch_scan8q_rounds<16>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 20: launch_scan8q_rounds<20>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 22: launch_scan8q_rounds<22>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan8q_rounds<24>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
     }
 }
 
@@ -804,10 +834,10 @@ inline int effective_variant(int M, int variant, int64_t N, int K, const uint8_t
     if (M == 8) {
         const bool ok8 = img32 && ((uintptr_t)codes & 7) == 0;
         if (special && !ok8) return 0;
-        // 65536 residue classes: regrouping pays once most classes hold a few dozen codes
-        // (two lanes per code, variants 80..84, are no faster here: an LDS access then holds two groups of four codes, and
-        // with 12 % of the groups left over from the matching its conflicts double: 0.61 of the LDS peak either way)
-        if (variant == 0 && ok8 && K >= 256 && N >= ((int64_t)1 << 22)) return 70;
+        // 65536 residue classes: regrouping pays once most classes hold a few dozen codes; then two lanes per code
+        // (an LDS access holds two groups of four codes, so the left-over groups cost it more than the four-lane scan
+        // 70, but a tile fill serves twice the codes: 0.63 against 0.60 of the LDS peak at N = 1e7, K = 1e4)
+        if (variant == 0 && ok8 && K >= 256 && N >= ((int64_t)1 << 22)) return choose_scan8_large(N, K);
         if (variant == 0) {
             // skewed scan: while one round of workgroups covers the codes, the smallest shape that does so (measured
             // per round at K = 1000: 139, 172, 220, 263 us for 512, 1024, 1536, 2048 codes per workgroup)
@@ -952,7 +982,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             }
         } else if (M == 8 && variant_two_lane(M, variant))
             launch_scan_grouped8_q(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
-                                   assign + n0, dist ? dist + n0 : nullptr, st, rl);
+                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, 0);
         else if (variant_lds_loads(M, variant))
             launch_scan_grouped_h(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);

@@ -665,6 +665,20 @@ __device__ __forceinline__ uint32_t code_class(uint32_t pk)
     return (pk & 3u) | ((pk >> 6) & 0xcu) | ((pk >> 12) & 0x30u) | ((pk >> 18) & 0xc0u);
 }
 
+// The codes left over by the matching are dealt to groups by quarters of their list: member k of a left-over group
+// is the code at the same place of quarter k.  The list is therefore ordered by a key under which, if the quarters are
+// balanced, codes at the same place of different quarters differ mod 4 in every subspace: the top digit (2 bits) is
+// the residue of the last subspace, every other digit that subspace's residue plus the top digit, mod 4.  The deeper
+// a digit, the sooner uneven class sizes put the quarters out of step; the first few subspaces are what is gained.
+// This is the key's inverse: the class (2 bits per subspace) that holds place `key` of the order.
+__device__ __forceinline__ uint32_t leftover_order_class(uint32_t key, int nsub)
+{
+    const uint32_t top = key >> (2 * (nsub - 1));
+    uint32_t c = top << (2 * (nsub - 1));
+    for (int s = 0; s < nsub - 1; ++s) c |= (((key >> (2 * s)) - top) & 3u) << (2 * s);
+    return c;
+}
+
 // position of slot `slot` of group `u` (counting residue and left-over groups in their final order): groups
 // 2b and 2b+1 share the block of 8 slots b and take the slots the LDS serves together
 __device__ __forceinline__ int64_t group_slot_position(int64_t u, uint32_t slot)
@@ -798,17 +812,20 @@ __global__ __launch_bounds__(1024) void code_group_plan_kernel(GroupPlan* __rest
         plan->gbase[c2][d] = base;
         plan->gbase[c3][d] = base;
     }
-    // --- left-overs: exclusive prefix over classes in ascending order, lane j owns classes 4j .. 4j+3
+    // --- left-overs: exclusive prefix over the classes in the order of leftover_order_class, lane j owns places
+    //     4j .. 4j+3 of it
     {
-        const uint32_t c0 = (uint32_t)tid << 2;
-        const uint32_t l0 = rem[c0], l1 = rem[c0 + 1], l2 = rem[c0 + 2], l3 = rem[c0 + 3];
+        const uint32_t k0 = (uint32_t)tid << 2;
+        const uint32_t c0 = leftover_order_class(k0, 4), c1 = leftover_order_class(k0 + 1, 4),
+                       c2 = leftover_order_class(k0 + 2, 4), c3 = leftover_order_class(k0 + 3, 4);
+        const uint32_t l0 = rem[c0], l1 = rem[c1], l2 = rem[c2], l3 = rem[c3];
         const uint32_t mine = l0 + l1 + l2 + l3;
         const uint32_t inc = wave_inclusive_scan(mine);
         uint32_t e = inc - mine;
-        plan->first[c0][GROUP_ROUNDS] = tot[c0] - l0;          plan->lbase[c0] = e;      e += l0;
-        plan->first[c0 + 1][GROUP_ROUNDS] = tot[c0 + 1] - l1;  plan->lbase[c0 + 1] = e;  e += l1;
-        plan->first[c0 + 2][GROUP_ROUNDS] = tot[c0 + 2] - l2;  plan->lbase[c0 + 2] = e;  e += l2;
-        plan->first[c0 + 3][GROUP_ROUNDS] = tot[c0 + 3] - l3;  plan->lbase[c0 + 3] = e;
+        plan->first[c0][GROUP_ROUNDS] = tot[c0] - l0;  plan->lbase[c0] = e;  e += l0;
+        plan->first[c1][GROUP_ROUNDS] = tot[c1] - l1;  plan->lbase[c1] = e;  e += l1;
+        plan->first[c2][GROUP_ROUNDS] = tot[c2] - l2;  plan->lbase[c2] = e;  e += l2;
+        plan->first[c3][GROUP_ROUNDS] = tot[c3] - l3;  plan->lbase[c3] = e;
         if (tid == 63) {
             const uint32_t ltot = inc, lg = (ltot + 3u) / 4u;
             plan->groups = gtot;
@@ -1916,20 +1933,23 @@ __global__ __launch_bounds__(1024) void code8_group_plan_kernel(GroupPlan8* __re
         gtot += round_total;
         __syncthreads();               // rem[d+1] complete; wsum, sbase, round_total free for the next round
     }
-    // left-overs: exclusive prefix over classes in ascending order, thread t owns classes 64t .. 64t+63
+    // left-overs: exclusive prefix over the classes in the order of leftover_order_class, thread t owns places
+    // 64t .. 64t+63 of it
     {
         constexpr int CPT = GROUP8_CLASSES / 1024;
         uint32_t mine = 0;
         for (int i = 0; i < CPT; ++i)
-            mine += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][tid * CPT + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            mine += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][leftover_order_class((uint32_t)(tid * CPT + i), 8)],
+                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const uint32_t inc = wave_inclusive_scan(mine);
         if ((tid & 63) == 63) wsum[0][wv] = inc;
         __syncthreads();
         uint32_t e = inc - mine;
         for (int w = 0; w < wv; ++w) e += wsum[0][w];
         for (int i = 0; i < CPT; ++i) {
-            plan->lbase[tid * CPT + i] = e;
-            e += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][tid * CPT + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t cls = leftover_order_class((uint32_t)(tid * CPT + i), 8);
+            plan->lbase[cls] = e;
+            e += __hip_atomic_load(&plan->rem[GROUP_ROUNDS][cls], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (tid == 1023) {
             const uint32_t ltot = e, lg = (ltot + 3u) / 4u;
