@@ -587,7 +587,7 @@ void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const
 
 // M = 4, many codes: the four-lane scan (variant 70) or one of the shapes of the LDS-direct scan (85..87), by the time
 // the rounds of workgroups take.  Clocks per tile and workgroup of C codes, from the measured times: four lanes per
-// code 2.30 C + 2065 (the fill of 128 KB between two barriers), LDS-direct 2.53 C + 1064 (two halves).
+// code 2.30 C + 2065 (the fill of 128 KB between two barriers), LDS-direct 2.45 C + 1064 (two halves).
 int choose_scan4_large(int64_t n)
 {
     const int ncu = cu_count();
@@ -600,7 +600,7 @@ int choose_scan4_large(int64_t n)
     static const int cand[] = {85, 87, 86};
     for (int v : cand) {
         const int64_t C = scan4h_codes_per_workgroup(v);
-        const double cost = (double)rounds(C) * (2.53 * (double)C + 1064.0);
+        const double cost = (double)rounds(C) * (2.45 * (double)C + 1064.0);
         if (cost < best_cost) { best_cost = cost; best = v; }
     }
     return best;
@@ -668,7 +668,7 @@ int scan8q_codes_per_slot(int64_t n_alloc, int64_t* cost_out)
 }
 
 // M = 8, many codes: four lanes per code (variant 70) or two (80), by the time the rounds take.  Per unit the
-// two-lane scan is about 3 % slower (the left-over groups' conflicts), and with few tiles its longer epilogue shows.
+// two-lane scan is about 5 % faster (74 against 79 us at N = 1e7, K = 1e4); with few tiles its longer epilogue shows.
 int choose_scan8_large(int64_t n, int K)
 {
     if (K < 512) return 70;
@@ -679,7 +679,7 @@ int choose_scan8_large(int64_t n, int K)
     const int64_t cost_p = ((wgs + ncu - 1) / ncu) * (R + 9);
     int64_t cost_q = 0;
     scan8q_codes_per_slot(na, &cost_q);
-    return (double)cost_q * 1.03 < (double)cost_p ? 80 : 70;
+    return (double)cost_q * 0.95 < (double)cost_p ? 80 : 70;
 }
 
 // M = 8 scan over regrouped codes with two-lane slots (256 R codes per workgroup): variants 80..84

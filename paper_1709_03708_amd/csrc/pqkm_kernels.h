@@ -679,6 +679,29 @@ __device__ __forceinline__ uint32_t leftover_order_class(uint32_t key, int nsub)
     return c;
 }
 
+// Place of residue group g / of left-over group jg in the final order of all groups (gtot residue groups, lg left-over
+// groups, dm1 = gtot / lg).  The left-over groups are spread evenly among the residue groups, so that every workgroup
+// gets its share of their bank conflicts: one after every dm1 residue groups for the four-lane scans; for the
+// two-lane scans, whose LDS accesses hold the groups 2i and 2i + 1 together, two after every 2 dm1 (pairs != 0): two
+// left-over groups that share their accesses cost about the conflicts of one.
+__device__ __forceinline__ int64_t residue_group_place(uint32_t g, uint32_t lg, uint32_t dm1, int pairs)
+{
+    if (!dm1) return g;
+    if (!pairs) {
+        const uint32_t before = g / dm1;
+        return (int64_t)g + (before < lg ? before : lg);
+    }
+    const uint32_t before = 2u * (g / (2u * dm1)), all = lg & ~1u;
+    return (int64_t)g + (before < all ? before : all);
+}
+__device__ __forceinline__ int64_t leftover_group_place(uint32_t jg, uint32_t gtot, uint32_t lg, uint32_t dm1, int pairs)
+{
+    if (!dm1) return (int64_t)gtot + jg;
+    if (!pairs) return (int64_t)jg * (dm1 + 1) + dm1;
+    if (jg < (lg & ~1u)) return (int64_t)(jg >> 1) * (2 * dm1 + 2) + 2 * dm1 + (jg & 1u);
+    return (int64_t)gtot + lg - 1;                  // an odd one out closes the list
+}
+
 // position of slot `slot` of group `u` (counting residue and left-over groups in their final order): groups
 // 2b and 2b+1 share the block of 8 slots b and take the slots the LDS serves together
 __device__ __forceinline__ int64_t group_slot_position(int64_t u, uint32_t slot)
@@ -871,16 +894,14 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
             }
             const uint32_t g = gbase_s[c][d] + (rank - first_s[c][d]);
             slot = c & 3u;
-            uint32_t before = dm1 ? g / dm1 : 0u;     // left-over groups placed before this group
-            if (before > lg) before = lg;
-            u = (int64_t)g + before;
+            u = residue_group_place(g, lg, dm1, blocks_of_16);
         } else {
-            // left-overs come sorted by class: group j takes the left-overs j, j + lg, j + 2 lg, j + 3 lg, four
-            // different stretches of that order, rather than four neighbours of (mostly) one class
+            // left-overs come in the order of leftover_order_class: group j takes the left-overs j, j + lg, j + 2 lg,
+            // j + 3 lg, four different stretches of that order, rather than four neighbours of (mostly) one class
             const uint32_t li = lbase_s[c] + (rank - first_s[c][GROUP_ROUNDS]);
             const uint32_t jg = li % lg;
             slot = li / lg;
-            u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+            u = leftover_group_place(jg, gtot, lg, dm1, blocks_of_16);
         }
         const int64_t pos = blocks_of_16 ? group_slot_position16(u, slot) : group_slot_position(u, slot);
         if (pos < n_alloc) gco[pos] = make_uint2(pk, (uint32_t)i);
@@ -895,8 +916,7 @@ __global__ __launch_bounds__(GROUP_THREADS) void code_group_scatter_kernel(const
             const uint32_t li = ltot + (uint32_t)tid;
             if (li < 4u * lg) {
                 const uint32_t jg = li % lg;
-                const int64_t ul = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
-                pos = group_slot_position(ul, li / lg);
+                pos = group_slot_position(leftover_group_place(jg, gtot, lg, dm1, 0), li / lg);
             }
         } else if (tid < 8) {
             if (T & 1) pos = group_slot_position(T, (uint32_t)tid - 4);
@@ -1987,14 +2007,12 @@ __global__ __launch_bounds__(256) void code8_group_scatter_kernel(const uint8_t*
                 if (rank >= tot - plan->rem[d + step][c]) d += step;
             const uint32_t g = plan->gbase[d][c] + (rank - (tot - plan->rem[d][c]));
             slot = c & 3u;
-            uint32_t before = dm1 ? g / dm1 : 0u;
-            if (before > lg) before = lg;
-            u = (int64_t)g + before;
+            u = residue_group_place(g, lg, dm1, blocks_of_16);
         } else {
             const uint32_t li = plan->lbase[c] + (rank - (tot - left));
             const uint32_t jg = li % lg;
             slot = li / lg;
-            u = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
+            u = leftover_group_place(jg, gtot, lg, dm1, blocks_of_16);
         }
         const int64_t pos = blocks_of_16 ? group_slot_position16(u, slot) : group_slot_position(u, slot);
         if (pos < n_alloc) gc8[pos] = make_uint4(v.x, v.y, (uint32_t)i, 0u);
@@ -2008,8 +2026,7 @@ __global__ __launch_bounds__(256) void code8_group_scatter_kernel(const uint8_t*
             const uint32_t li = ltot + (uint32_t)tid;
             if (li < 4u * lg) {
                 const uint32_t jg = li % lg;
-                const int64_t ul = dm1 ? (int64_t)jg * (dm1 + 1) + dm1 : (int64_t)gtot + jg;
-                pos = group_slot_position(ul, li / lg);
+                pos = group_slot_position(leftover_group_place(jg, gtot, lg, dm1, 0), li / lg);
             }
         } else if (tid < 8) {
             if (T & 1) pos = group_slot_position(T, (uint32_t)tid - 4);
