@@ -688,9 +688,10 @@ void launch_scan8q_rounds(const uint4* gc8, int64_t n_alloc, const float4* img, 
                           float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
 {
     // one kernel launch per rounds_per_launch rounds of workgroups (see launch_scan4q_rounds), 0 = one for all.
-    // The caller passes 0: measured at N = 1e7, K = 1e4, a launch per round is 4 % slower for this scan (0.606
-    // against 0.631 of the LDS peak): every round then waits for its slowest workgroup, and the conflicts of the
-    // left-over groups make the workgroups of this scan uneven.
+    // (While the left-over groups were spread singly, a launch per round was 4 % slower for this scan: every round
+    // waits for its slowest workgroup, and their conflicts made the workgroups uneven.  Placed in pairs they cost
+    // half, and the two ways take the same time, 0.68 of the LDS peak at N = 1e7, K = 1e4; a launch per round moves
+    // less memory.)
     constexpr int64_t C = 256 * (int64_t)R;
     const int64_t nwg = (n_alloc + C - 1) / C;
     const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
@@ -982,7 +983,7 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             }
         } else if (M == 8 && variant_two_lane(M, variant))
             launch_scan_grouped8_q(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
-                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, 0);
+                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
         else if (variant_lds_loads(M, variant))
             launch_scan_grouped_h(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
