@@ -580,9 +580,22 @@ void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const
         case 86: launch_scan4h_rounds<12, 1024, 4>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
         case 87: launch_scan4h_rounds<14, 1024, 3>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
         case 88: launch_scan4h_rounds<32, 512, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        case 89: launch_scan4h_rounds<8, 1024, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 89: launch_scan4h_rounds<8, 1024, 3>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
         default: launch_scan4h_rounds<16, 1024, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
     }
+}
+
+// The 4096-code shape of the LDS-direct scan, filing (code, center) records by cluster group for the histogram: all
+// workgroups in one launch (a segment is named by its workgroup's index in the grid).
+void launch_scan4h_bucket(const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows, int ntiles,
+                          int32_t* assign, float* dist, hipStream_t st, BucketOut bo, int* nwg_out)
+{
+    constexpr int64_t C = 512 * 8;
+    const int64_t nwg = (n_alloc + C - 1) / C;
+    hipLaunchKernelGGL((assign_scan4h_kernel<8, 1024, 3, true>), dim3((unsigned)nwg), dim3(1024), 0, st, n_alloc, gco, img,
+                       rows, ntiles, assign, dist, RankOut{}, bo);
+    ++t_scan_kernels;
+    *nwg_out = (int)nwg;
 }
 
 // M = 4, many codes: the four-lane scan (variant 70) or one of the shapes of the LDS-direct scan (85..87), by the time
@@ -904,9 +917,13 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int variant = effective_variant(M, opt.scan_variant, N, K, codes);
     // No records to file for the histogram: from a few rounds of workgroups on, the scan with two-lane slots whose
     // tiles are loaded straight into LDS, half a tile ahead, in the shape that the rounds favour
-    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 21) &&
-        !(link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off))
+    // Records to file (the fused iteration at owner-path sizes): the same scan in its 4096-code shape, which files
+    // them as the four-lane scan does.
+    const bool files_records = M == 4 && link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off;
+    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 21) && !files_records)
         variant = choose_scan4_large(N);
+    else if (M == 4 && variant == 70 && opt.scan_variant == 0 && files_records)
+        variant = 89;
     const int layout = variant_layout(M, variant);
     const bool sliding = variant_sliding(M, variant);
     if (sliding) {
@@ -984,7 +1001,13 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
         } else if (M == 8 && variant_two_lane(M, variant))
             launch_scan_grouped8_q(variant, gc8, group_alloc(cnt), reinterpret_cast<const float4*>(img), (int)ntiles,
                                    assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
-        else if (variant_lds_loads(M, variant))
+        else if (variant == 89 && files_records && N <= per_launch) {
+            BucketOut bo{reinterpret_cast<uint2*>(ws + c.pool_off), reinterpret_cast<uint2*>(ws + c.bseg_off), link->KT,
+                         link->ngroups};
+            launch_scan4h_bucket(gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
+                                 assign + n0, dist ? dist + n0 : nullptr, st, bo, &link->nwg);
+            link->produced = true;
+        } else if (variant_lds_loads(M, variant))
             launch_scan_grouped_h(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
         else if (variant_two_lane(M, variant))

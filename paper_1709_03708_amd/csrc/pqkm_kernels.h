@@ -1582,12 +1582,12 @@ __device__ __forceinline__ void buffer_to_lds16(uint32_t lds_addr, v4i rsrc, uin
 }
 __device__ __forceinline__ void wait_vector_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int R, int THREADS, int DEPTH>
+template <int R, int THREADS, int DEPTH, bool BUCKET = false>
 __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const uint2* __restrict__ gco,
                                                             const float4* __restrict__ img,
                                                             const float4* __restrict__ rows, int ntiles,
                                                             int32_t* __restrict__ assign, float* __restrict__ dist,
-                                                            RankOut ro)
+                                                            RankOut ro, BucketOut bo = BucketOut{})
 {
     constexpr int LPS = 2, TK = 32;
     constexpr int SLOTS = THREADS / LPS;
@@ -1595,6 +1595,11 @@ __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const
     constexpr uint32_t HPLANE = 16384;      // bytes per (m, h) plane: 256 subcodes x 16 centers
     static_assert(R % 2 == 0, "the epilogue gives every lane R / 2 codes");
     static_assert(C * 8 <= TILE_BYTES, "one 8-byte record per code must fit the tile buffer");
+    static_assert(!BUCKET || C * 24 <= TILE_BYTES, "BUCKET: 16 more bytes per code behind the records");
+    // BUCKET: the workgroup also files its codes by cluster group for the histogram, as assign_scan4p_kernel does
+    // (the whole grid must be one launch: segment (g, w) is named by blockIdx.x and gridDim.x)
+    __shared__ uint32_t gcnt[BUCKET ? 256 : 1];
+    __shared__ uint32_t gbase[BUCKET ? 256 : 1];
 
     __shared__ float4 tile[TILE_F4];
     const char* tb = reinterpret_cast<const char*>(tile);
@@ -1707,6 +1712,7 @@ __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const
     // center index with that sum is kept.
     constexpr int CPL = R / 2;
     constexpr int TNONE = 0x7fffffff;
+    if (BUCKET && tid < 256) gcnt[tid] = 0u;
     __syncthreads();
     {
         uint2* rec = reinterpret_cast<uint2*>(tile);
@@ -1781,6 +1787,40 @@ __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const
             assign[og] = kw;
             if (dist) dist[og] = sm;
             if (ro.count) ro.rank[og] = atomicAdd(&ro.count[kw], 1u);
+        }
+        if (BUCKET) {
+            // behind the 8-byte records: the code, its center, its cluster group and its rank among the workgroup's
+            // codes of that group
+            const uint32_t k = (bi == IDX_NONE) ? 0u : (uint32_t)bi;
+            uint32_t g = 0xffffffffu, rank = 0u;
+            if (og != ORIGIN_NONE) {
+                g = k / (uint32_t)bo.KT;
+                g = g < 255u ? g : 255u;                         // k < K and at most 255 groups: never taken
+                rank = atomicAdd(&gcnt[g], 1u);
+            }
+            *reinterpret_cast<uint4*>(reinterpret_cast<char*>(tile) + (size_t)C * 8 + (size_t)jj * 16u) = make_uint4(pk, k, g, rank);
+        }
+    }
+    if (BUCKET) {
+        __syncthreads();
+        if (tid < 64) {                                          // exclusive prefix over the groups: lane l owns 4l .. 4l+3
+            const uint32_t a0 = gcnt[4 * tid], a1 = gcnt[4 * tid + 1], a2 = gcnt[4 * tid + 2], a3 = gcnt[4 * tid + 3];
+            const uint32_t mine = a0 + a1 + a2 + a3;
+            const uint32_t e0 = wave_inclusive_scan(mine) - mine, e1 = e0 + a0, e2 = e1 + a1, e3 = e2 + a2;
+            gbase[4 * tid] = e0;  gbase[4 * tid + 1] = e1;  gbase[4 * tid + 2] = e2;  gbase[4 * tid + 3] = e3;
+            const size_t nw = gridDim.x;
+            uint2* sg = bo.seg + blockIdx.x;
+            if (4 * tid < bo.ngroups) sg[(size_t)(4 * tid) * nw] = make_uint2((uint32_t)(base + e0), a0);
+            if (4 * tid + 1 < bo.ngroups) sg[(size_t)(4 * tid + 1) * nw] = make_uint2((uint32_t)(base + e1), a1);
+            if (4 * tid + 2 < bo.ngroups) sg[(size_t)(4 * tid + 2) * nw] = make_uint2((uint32_t)(base + e2), a2);
+            if (4 * tid + 3 < bo.ngroups) sg[(size_t)(4 * tid + 3) * nw] = make_uint2((uint32_t)(base + e3), a3);
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int i = 0; i < CPL; ++i) {
+            const int j = i * THREADS + tid;
+            const uint4 r = *reinterpret_cast<const uint4*>(tb + (size_t)C * 8 + (size_t)j * 16u);
+            if (r.z != 0xffffffffu) bo.pool[base + gbase[r.z] + r.w] = make_uint2(r.x, r.y);
         }
     }
 }
