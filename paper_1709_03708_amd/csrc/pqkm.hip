@@ -598,7 +598,7 @@ void launch_scan4h_bucket(const uint2* gco, int64_t n_alloc, const float4* img, 
     *nwg_out = (int)nwg;
 }
 
-// M = 4, many codes: the four-lane scan (variant 70) or one of the shapes of the LDS-direct scan (85..87), by the time
+// M = 4, many codes: the four-lane scan (variant 70) or one of the shapes of the LDS-direct scan (85..87, 89), by the time
 // the rounds of workgroups take.  Clocks per tile and workgroup of C codes, from the measured times: four lanes per
 // code 2.30 C + 2065 (the fill of 128 KB between two barriers), LDS-direct 2.45 C + 1064 (two halves).
 int choose_scan4_large(int64_t n)
@@ -610,7 +610,7 @@ int choose_scan4_large(int64_t n)
     double best_cost = (double)rounds(c4p) * (2.30 * (double)c4p + 2065.0);
     int best = 70;
     if (n >= ((int64_t)1 << 23)) return 85;            // stretches are cut to whole rounds of the largest shape
-    static const int cand[] = {85, 87, 86};
+    static const int cand[] = {85, 87, 86, 89};
     for (int v : cand) {
         const int64_t C = scan4h_codes_per_workgroup(v);
         const double cost = (double)rounds(C) * (2.45 * (double)C + 1064.0);
@@ -915,12 +915,12 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
     int64_t ntiles = ((int64_t)K + TK - 1) / TK;
     int64_t total = ntiles * (int64_t)(TILE_BYTES / 4);
     int variant = effective_variant(M, opt.scan_variant, N, K, codes);
-    // No records to file for the histogram: from a few rounds of workgroups on, the scan with two-lane slots whose
-    // tiles are loaded straight into LDS, half a tile ahead, in the shape that the rounds favour
+    // No records to file for the histogram: the four-lane scan or the scan with two-lane slots whose tiles are loaded
+    // straight into LDS, half a tile ahead, in the shape that the rounds favour
     // Records to file (the fused iteration at owner-path sizes): the same scan in its 4096-code shape, which files
     // them as the four-lane scan does.
     const bool files_records = M == 4 && link && link->wanted && N <= GROUP_CHUNK_MAX - 16384 && c.bseg_off != c.pool_off;
-    if (M == 4 && variant == 70 && opt.scan_variant == 0 && N >= ((int64_t)1 << 21) && !files_records)
+    if (M == 4 && variant == 70 && opt.scan_variant == 0 && !files_records)
         variant = choose_scan4_large(N);
     else if (M == 4 && variant == 70 && opt.scan_variant == 0 && files_records)
         variant = 89;

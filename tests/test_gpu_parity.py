@@ -666,19 +666,21 @@ def _run_config_full(env, cfg, iters, **over):
                                       (550_003, 600, "one_class"), (525_000, 4000, "templates"),
                                       (560_001, 500, "several_launches"), (560_001, 500, "forced_owner"),
                                       (70_001, 130, "templates"), (300_007, 1000, "templates"),
-                                      (4_500_000, 300, "templates")])
+                                      (4_500_000, 300, "templates"), (600_007, 1000, "four_lane"),
+                                      (525_000, 4000, "four_lane"), (540_672, 257, "four_lane")])
 def test_fit_files_codes_by_cluster_group(env, N, K, kind):
     """pqkm_fit with 4-byte codes at owner-path sizes: above one round of 2048-code workgroups (256 x 2048 codes) the
     regrouped scan runs and files (code, center) records by cluster group; the vote counts from those itself when
     a group has at most 16 clusters and there are at most 1024 scan workgroups, else the histogram kernel does
     (K = 4000: 32 clusters per group; N = 4.5e6: more scan workgroups).  The two smaller cases take the skewed
-    scan and the separate histogram pass through the same call.  Centers, assignments, histograms and counts of the last iteration against
+    scan and the separate histogram pass through the same call.  The filing scan is the one that loads its half tiles
+    straight into LDS; "four_lane" forces the four-lane scan, which files the same records.  Centers, assignments, histograms and counts of the last iteration against
     the oracle, for ragged N and K, cluster sizes from empty to huge, and codes of a single residue class."""
     pq, oracle, W = env["pq"], env["oracle"], env["W"]
     rng = np.random.default_rng(N + K)
     w = workload(2, N=N, K=K)
     tables = env["oracle"].build_tables(W.codewords(w))
-    if kind in ("templates", "several_launches", "forced_owner"):
+    if kind in ("templates", "several_launches", "forced_owner", "four_lane"):
         codes = W.codes_numpy(w)
     elif kind == "skewed":
         # nine tenths of the codes are copies of 3 codes: a few huge clusters, most groups nearly empty
@@ -701,12 +703,15 @@ def test_fit_files_codes_by_cluster_group(env, N, K, kind):
         pq.set_option("launch_codes_log2", 16)
     if kind == "forced_owner":
         pq.set_option("hist_kernel", 2)
+    if kind == "four_lane":
+        pq.set_option("scan_variant", 70)
     try:
         _, fa = pq.fit(d_codes, d_tables, d_cent, iters, hist=hist, counts=counts)
         _sync(env)
     finally:
         pq.set_option("launch_codes_log2", 26)
         pq.set_option("hist_kernel", 0)
+        pq.set_option("scan_variant", 0)
     rc, ra, rh, rcnt = oracle.fit(codes, tables, cent0, iters)
     np.testing.assert_array_equal(fa.cpu().numpy(), ra)
     np.testing.assert_array_equal(u32(hist), rh)
