@@ -559,7 +559,7 @@ inline int64_t scan4h_codes_per_workgroup(int variant)
 
 template <int R, int THREADS, int DEPTH>
 void launch_scan4h_rounds(const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows, int ntiles,
-                          int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+                          int nhalves, int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
 {
     // one kernel launch per rounds_per_launch rounds of workgroups (see launch_scan4q_rounds)
     constexpr int64_t C = (THREADS / 2) * (int64_t)R;
@@ -568,32 +568,33 @@ void launch_scan4h_rounds(const uint2* gco, int64_t n_alloc, const float4* img, 
     for (int64_t w0 = 0; w0 < nwg; w0 += per) {
         const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
         hipLaunchKernelGGL((assign_scan4h_kernel<R, THREADS, DEPTH>), dim3((unsigned)cnt), dim3(THREADS), 0, st,
-                           n_alloc - w0 * C, gco + w0 * C, img, rows, ntiles, assign, dist, ro);
+                           n_alloc - w0 * C, gco + w0 * C, img, rows, ntiles, nhalves, assign, dist, ro);
         ++t_scan_kernels;
     }
 }
 
 void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows,
-                           int ntiles, int32_t* assign, float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
+                           int ntiles, int nhalves, int32_t* assign, float* dist, hipStream_t st, RankOut ro,
+                           int rounds_per_launch)
 {
     switch (variant) {
-        case 86: launch_scan4h_rounds<12, 1024, 4>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        case 87: launch_scan4h_rounds<14, 1024, 3>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        case 88: launch_scan4h_rounds<32, 512, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        case 89: launch_scan4h_rounds<8, 1024, 3>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        default: launch_scan4h_rounds<16, 1024, 2>(gco, n_alloc, img, rows, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        case 86: launch_scan4h_rounds<12, 1024, 4>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
+        case 87: launch_scan4h_rounds<14, 1024, 3>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
+        case 88: launch_scan4h_rounds<32, 512, 2>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
+        case 89: launch_scan4h_rounds<8, 1024, 3>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan4h_rounds<16, 1024, 2>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
     }
 }
 
 // The 4096-code shape of the LDS-direct scan, filing (code, center) records by cluster group for the histogram: all
 // workgroups in one launch (a segment is named by its workgroup's index in the grid).
 void launch_scan4h_bucket(const uint2* gco, int64_t n_alloc, const float4* img, const float4* rows, int ntiles,
-                          int32_t* assign, float* dist, hipStream_t st, BucketOut bo, int* nwg_out)
+                          int nhalves, int32_t* assign, float* dist, hipStream_t st, BucketOut bo, int* nwg_out)
 {
     constexpr int64_t C = 512 * 8;
     const int64_t nwg = (n_alloc + C - 1) / C;
     hipLaunchKernelGGL((assign_scan4h_kernel<8, 1024, 3, true>), dim3((unsigned)nwg), dim3(1024), 0, st, n_alloc, gco, img,
-                       rows, ntiles, assign, dist, RankOut{}, bo);
+                       rows, ntiles, nhalves, assign, dist, RankOut{}, bo);
     ++t_scan_kernels;
     *nwg_out = (int)nwg;
 }
@@ -1005,11 +1006,11 @@ pqkm_status assign_tiled(const uint8_t* codes, int64_t N, const uint8_t* centers
             BucketOut bo{reinterpret_cast<uint2*>(ws + c.pool_off), reinterpret_cast<uint2*>(ws + c.bseg_off), link->KT,
                          link->ngroups};
             launch_scan4h_bucket(gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
-                                 assign + n0, dist ? dist + n0 : nullptr, st, bo, &link->nwg);
+                                 (K + 15) / 16, assign + n0, dist ? dist + n0 : nullptr, st, bo, &link->nwg);
             link->produced = true;
         } else if (variant_lds_loads(M, variant))
             launch_scan_grouped_h(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
-                                  assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
+                                  (K + 15) / 16, assign + n0, dist ? dist + n0 : nullptr, st, rl, opt.rounds_per_launch);
         else if (variant_two_lane(M, variant))
             launch_scan_grouped_q(variant, gco, group_alloc(cnt), reinterpret_cast<const float4*>(img), rows, (int)ntiles,
                                   assign + n0, dist ? dist + n0 : nullptr, st, rl, tsrc, opt.rounds_per_launch);

@@ -1585,7 +1585,7 @@ __device__ __forceinline__ void wait_vector_loads() { asm volatile("s_waitcnt vm
 template <int R, int THREADS, int DEPTH, bool BUCKET = false>
 __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const uint2* __restrict__ gco,
                                                             const float4* __restrict__ img,
-                                                            const float4* __restrict__ rows, int ntiles,
+                                                            const float4* __restrict__ rows, int ntiles, int nhalves,
                                                             int32_t* __restrict__ assign, float* __restrict__ dist,
                                                             RankOut ro, BucketOut bo = BucketOut{})
 {
@@ -1654,10 +1654,12 @@ __global__ __launch_bounds__(THREADS) void assign_scan4h_kernel(int64_t N, const
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             // this half has arrived (own loads, then everybody's), and nobody reads the other buffer any more
+            // (nhalves = the halves that hold a center, 2 ntiles or one less: an all-padding last half is not scanned)
+            if (2 * t + h >= nhalves) break;
             wait_vector_loads();
             __syncthreads();
             const int tf = h ? t + 1 : t, hf = h ^ 1;                // the half after this one
-            const bool more = tf < ntiles;
+            const bool more = 2 * t + h + 1 < nhalves;
             auto issue = [&](int step) -> Pair {
                 const int r = step / 4, m = step % 4;
                 const uint32_t ad = (m == 0) ? unpack_low15(low15, pa[r])
