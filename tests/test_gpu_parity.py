@@ -479,6 +479,45 @@ def test_random_shapes_forced_large_input_scans(env, seed):
         np.testing.assert_array_equal(d_cent.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("M,N,K,variant", [(4, 4_700_003, 700, 85), (4, 2_500_001, 700, 89), (8, 3_100_007, 600, 80),
+                                           (8, 1_300_003, 600, 70), (32, 1_700_001, 300, 53), (16, 2_300_003, 300, 51)])
+def test_rounds_per_launch_do_not_change_results(env, M, N, K, variant):
+    """The large scans issue their workgroups in kernel launches of one round (one workgroup per compute unit) each by
+    default.  Several rounds of workgroups, a ragged last one: the assignment with one round per launch against the
+    oracle on a sample of the codes, and every code bit for bit against the same scan issued two rounds per launch
+    and as a single launch."""
+    pq, oracle, W, torch = env["pq"], env["oracle"], env["W"], env["torch"]
+    w = workload(2 if M == 4 else 3, N=N, K=K, M=M, D=16 * M)
+    codes = W.codes_numpy(w)
+    centers = codes[W.init_center_indices(w)].copy()
+    tables = oracle.build_tables(W.codewords(w))
+    d_codes, d_cent, d_tab = _dev(env, codes), _dev(env, centers), _dev(env, tables)
+    res = {}
+    pq.set_option("assign_kernel", 2)
+    pq.set_option("scan_variant", variant)
+    try:
+        for rpl in (1, 2, 0):
+            progress(f"rounds per launch {rpl}: M={M} N={N} K={K} variant {variant}")
+            pq.set_option("scan_rounds_per_launch", rpl)
+            a = torch.full((N,), -1, dtype=torch.int32, device=env["dev"])
+            d = torch.full((N,), float("nan"), dtype=torch.float32, device=env["dev"])
+            pq.assign(d_codes, d_cent, d_tab, assign=a, dist=d)
+            _sync(env)
+            res[rpl] = (a.cpu().numpy(), d.cpu().numpy())
+    finally:
+        pq.set_option("scan_rounds_per_launch", 1)
+        pq.set_option("scan_variant", 0)
+        pq.set_option("assign_kernel", 0)
+    for rpl in (2, 0):
+        np.testing.assert_array_equal(res[rpl][0], res[1][0])
+        np.testing.assert_array_equal(res[rpl][1].view(np.uint32), res[1][1].view(np.uint32))
+    rng = np.random.default_rng(N)
+    pick = np.unique(np.concatenate([rng.integers(0, N, 20_000), np.arange(N - 3000, N), np.arange(3000)]))
+    ra, rd = oracle.assign(np.ascontiguousarray(codes[pick]), centers, tables)
+    np.testing.assert_array_equal(res[1][0][pick], ra)
+    np.testing.assert_array_equal(res[1][1][pick].view(np.uint32), rd.view(np.uint32))
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_shapes_fused_iteration(env, seed):
     """Seeded random shapes above one round of 2048-code workgroups (M = 4, K >= 128), where pqkm_fit runs the
