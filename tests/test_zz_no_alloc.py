@@ -26,6 +26,7 @@ def _case(cfg, N, K, **over):
 
 
 @pytest.mark.parametrize("cfg,sizes", [(2, [(600_007, 1000), (70_001, 130)]), (2, [(9_001, 77), (300, 5)]),
+                                       (2, [(1_500_000, 900), (600_007, 300)]),
                                        (3, [(200_003, 700), (5_001, 33)]), (4, [(20_001, 300), (1_000, 40)])])
 def test_noalloc_assign_matches_assign_twice_in_a_row(cfg, sizes):
     import torch
