@@ -664,12 +664,13 @@ void launch_scan_grouped8(int variant, const uint4* gc8, int64_t n_alloc, const 
 }
 
 // Codes per lane-slot of the two-lane M = 8 scan (a workgroup takes 256 R codes) by the rounds, in the unit of
-// scan8p_codes_per_slot (128 codes' reads per tile): 2 R + 13.  24 codes per lane-slot spill (9 registers) and are
-// 8 % slower per code: only when forced.
+// scan8p_codes_per_slot (128 codes' reads per tile): 2 R + 13.  24 codes per lane-slot fit the registers with the
+// reads of two steps in flight instead of three (0.692 of the LDS peak against 0.686 for 22 at whole rounds; with
+// three they spill and lose 8 %); 1024 threads with 10 or 8 codes per lane-slot reach 0.65 and 0.63.
 int scan8q_codes_per_slot(int64_t n_alloc, int64_t* cost_out)
 {
     const int ncu = cu_count();
-    static const int cand[] = {22, 20, 16};
+    static const int cand[] = {24, 22, 20, 16};
     int best = 22;
     int64_t best_cost = INT64_MAX;
     for (int r : cand) {
@@ -697,7 +698,7 @@ int choose_scan8_large(int64_t n, int K)
 }
 
 // M = 8 scan over regrouped codes with two-lane slots (256 R codes per workgroup): variants 80..84
-template <int R>
+template <int R, int THREADS = 512, int DEPTH = 3>
 void launch_scan8q_rounds(const uint4* gc8, int64_t n_alloc, const float4* img, int ntiles, int32_t* assign,
                           float* dist, hipStream_t st, RankOut ro, int rounds_per_launch)
 {
@@ -706,12 +707,12 @@ void launch_scan8q_rounds(const uint4* gc8, int64_t n_alloc, const float4* img, 
     // waits for its slowest workgroup, and their conflicts made the workgroups uneven.  Placed in pairs they cost
     // half, and the two ways take the same time, 0.68 of the LDS peak at N = 1e7, K = 1e4; a launch per round moves
     // less memory.)
-    constexpr int64_t C = 256 * (int64_t)R;
+    constexpr int64_t C = (THREADS / 2) * (int64_t)R;
     const int64_t nwg = (n_alloc + C - 1) / C;
     const int64_t per = rounds_per_launch > 0 ? (int64_t)rounds_per_launch * cu_count() : nwg;
     for (int64_t w0 = 0; w0 < nwg; w0 += per) {
         const int64_t cnt = nwg - w0 < per ? nwg - w0 : per;
-        hipLaunchKernelGGL((assign_scan8q_kernel<R, 512, 3>), dim3((unsigned)cnt), dim3(512), 0, st, n_alloc - w0 * C,
+        hipLaunchKernelGGL((assign_scan8q_kernel<R, THREADS, DEPTH>), dim3((unsigned)cnt), dim3(THREADS), 0, st, n_alloc - w0 * C,
                            gc8 + w0 * C, img, ntiles, assign, dist, ro);
         ++t_scan_kernels;
     }
@@ -732,7 +733,7 @@ void launch_scan_grouped8_q(int variant, const uint4* gc8, int64_t n_alloc, cons
         case 16: launch_scan8q_rounds<16>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
         case 20: launch_scan8q_rounds<20>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
         case 22: launch_scan8q_rounds<22>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
-        default: launch_scan8q_rounds<24>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan8q_rounds<24, 512, 2>(gc8, n_alloc, img, ntiles, assign, dist, st, ro, rounds_per_launch); break;
     }
 }
 
