@@ -582,7 +582,7 @@ void launch_scan_grouped_h(int variant, const uint2* gco, int64_t n_alloc, const
         case 87: launch_scan4h_rounds<14, 1024, 3>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
         case 88: launch_scan4h_rounds<32, 512, 2>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
         case 89: launch_scan4h_rounds<8, 1024, 3>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
-        default: launch_scan4h_rounds<16, 1024, 2>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
+        default: launch_scan4h_rounds<16, 1024, 3>(gco, n_alloc, img, rows, ntiles, nhalves, assign, dist, st, ro, rounds_per_launch); break;
     }
 }
 
